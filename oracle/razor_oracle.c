@@ -1,0 +1,248 @@
+/*
+ * RazorAttention reference oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, fp64 CPU statement of what the compressed-KV hot path
+ * computes, written from the paper (arXiv 2407.15891).  It shares no code,
+ * header, table or helper with the HIP library; only tests, the smoke check
+ * and the cpu_baseline leg of the benchmark may call it.
+ *
+ *   oracle_select       Algorithm 1, steps 2-3: which cache rows a head keeps
+ *   oracle_comp_token   Eq.(4): the compensation token (mean of dropped rows)
+ *   oracle_attn_head    Eq.(5): attention over kept rows + compensation token
+ *   oracle_decode_batch Algorithm 1, step 5: per-head dispatch over a batch
+ *
+ * No tiling, no online softmax, no fusion: two passes over the logits and
+ * straight sums, so every line can be held against the paper by eye.
+ * Inputs are read from their stored bits (bf16 or fp32) and widened to
+ * double without rounding.
+ *
+ * Parity status: the numeric value of Eq.(5) on general data is not printed
+ * anywhere in the paper ("parity unpinned" by a worked example); it is
+ * pinned through the special cases, closed forms and brute force listed in
+ * tests/test_oracle_pins.py.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+/* One stored element -> double (exact for both formats). */
+static double widen(const void *base, int dtype, int64_t idx)
+{
+    if (dtype == ORACLE_F32) {
+        return (double)((const float *)base)[idx];
+    } else {
+        uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
+        float f;
+        memcpy(&f, &bits, sizeof f);
+        return (double)f;
+    }
+}
+
+/*
+ * Algorithm 1, steps 2-3 (selection).  A retrieval head keeps every token.
+ * A non-retrieval head keeps the first n_sink tokens and the most recent
+ * `window` tokens; everything in between is the dropped set D = [d_lo, d_hi).
+ * When sinks and window already cover the sequence nothing is dropped
+ * (Eq.(4) would be 0/0), so the head is treated like a retrieval head.
+ * kept[] receives the kept positions in ascending order; returns their count.
+ */
+int64_t oracle_select(int64_t N, int retrieval, int64_t n_sink, int64_t window,
+                      int64_t *kept, int64_t *d_lo, int64_t *d_hi)
+{
+    int64_t n = 0;
+    if (retrieval || N <= n_sink + window) {
+        for (int64_t t = 0; t < N; ++t) kept[n++] = t;
+        *d_lo = 0;
+        *d_hi = 0;
+        return n;
+    }
+    for (int64_t t = 0; t < n_sink; ++t) kept[n++] = t;
+    for (int64_t t = N - window; t < N; ++t) kept[n++] = t;
+    *d_lo = n_sink;
+    *d_hi = N - window;
+    return n;
+}
+
+/*
+ * Eq.(4): khat = (1/N_d) sum_{m in D} k_m, vhat likewise, D = [d_lo, d_hi).
+ * K_head / V_head point at row 0 of one head; row stride in elements.
+ */
+void oracle_comp_token(const void *K_head, const void *V_head, int dtype,
+                       int64_t stride_n, int d, int64_t d_lo, int64_t d_hi,
+                       double *khat, double *vhat)
+{
+    int64_t N_d = d_hi - d_lo;
+    for (int c = 0; c < d; ++c) khat[c] = vhat[c] = 0.0;
+    for (int64_t m = d_lo; m < d_hi; ++m) {
+        for (int c = 0; c < d; ++c) {
+            khat[c] += widen(K_head, dtype, m * stride_n + c);
+            vhat[c] += widen(V_head, dtype, m * stride_n + c);
+        }
+    }
+    for (int c = 0; c < d; ++c) {
+        khat[c] /= (double)N_d;
+        vhat[c] /= (double)N_d;
+    }
+}
+
+/*
+ * Eq.(5) for one query vector q (length d):
+ *
+ *        N_d e^{q.khat} vhat + sum_{n kept} e^{q.k_n} v_n
+ *   o = ---------------------------------------------------
+ *        N_d e^{q.khat}      + sum_{n kept} e^{q.k_n}
+ *
+ * with every logit multiplied by `scale` (scale = 1 is the printed form).
+ * Kept rows come from two places: positions kept[0..n_kept) of the prefill
+ * cache (K_head/V_head, row stride stride_n) and n_new rows appended during
+ * decoding (K_new/V_new, row stride stride_new).  N_d == 0 means no
+ * compensation term (retrieval head, nothing dropped, or ablation).
+ * The exponentials are shifted by the largest logit, which cancels in the
+ * quotient.  scratch must hold n_kept + n_new doubles.
+ */
+void oracle_attn_head(const double *q, int d, double scale,
+                      const void *K_head, const void *V_head, int dtype,
+                      int64_t stride_n, const int64_t *kept, int64_t n_kept,
+                      const void *K_new, const void *V_new, int64_t stride_new,
+                      int64_t n_new,
+                      const double *khat, const double *vhat, int64_t N_d,
+                      double *scratch, double *out)
+{
+    int64_t n_rows = n_kept + n_new;
+    double s_c = 0.0, M = -INFINITY;
+
+    /* pass 1: logits */
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const void *kb = r < n_kept ? K_head : K_new;
+        int64_t off = r < n_kept ? kept[r] * stride_n : (r - n_kept) * stride_new;
+        double s = 0.0;
+        for (int c = 0; c < d; ++c) s += q[c] * widen(kb, dtype, off + c);
+        s *= scale;
+        scratch[r] = s;
+        if (s > M) M = s;
+    }
+    if (N_d > 0) {
+        for (int c = 0; c < d; ++c) s_c += q[c] * khat[c];
+        s_c *= scale;
+        /* the term N_d e^{s_c} equals e^{s_c + ln N_d}; only used to pick the shift */
+        if (s_c + log((double)N_d) > M) M = s_c + log((double)N_d);
+    }
+
+    /* pass 2: numerator and denominator */
+    double den = 0.0;
+    for (int c = 0; c < d; ++c) out[c] = 0.0;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const void *vb = r < n_kept ? V_head : V_new;
+        int64_t off = r < n_kept ? kept[r] * stride_n : (r - n_kept) * stride_new;
+        double e = exp(scratch[r] - M);
+        den += e;
+        for (int c = 0; c < d; ++c) out[c] += e * widen(vb, dtype, off + c);
+    }
+    if (N_d > 0) {
+        double e = (double)N_d * exp(s_c - M);
+        den += e;
+        for (int c = 0; c < d; ++c) out[c] += e * vhat[c];
+    }
+    for (int c = 0; c < d; ++c) out[c] /= den;
+}
+
+/*
+ * Algorithm 1, step 5 over a batch: query head j of sequence b uses KV head
+ * h = j / g (g = n_q_heads / n_kv_heads; a KV group shares one decision).
+ *
+ *   Q        [B, n_q_heads, d] stored dtype
+ *   K, V     prefill cache, element strides (stride_b, stride_h, stride_n)
+ *   kept     concatenated kept positions, head (b,h) owns
+ *            kept[kept_off[b*Hkv+h] .. kept_off[b*Hkv+h+1])
+ *   K_new,V_new [B, n_kv_heads, cap_new, d] appended rows, n_new of them valid
+ *   khat,vhat   [B, n_kv_heads, d] doubles;  N_d [B, n_kv_heads]
+ *   out      [B, n_q_heads, d] doubles
+ * Returns the number of threads used.
+ */
+int oracle_decode_batch(const void *Q, const void *K, const void *V, int dtype,
+                        int B, int n_q_heads, int n_kv_heads, int d,
+                        int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                        const int64_t *kept, const int64_t *kept_off,
+                        const void *K_new, const void *V_new, int64_t cap_new,
+                        int64_t n_new,
+                        const double *khat, const double *vhat,
+                        const int64_t *N_d, double scale, double *out)
+{
+    int g = n_q_heads / n_kv_heads;
+    int n_threads = 1;
+    int64_t esz = dtype == ORACLE_F32 ? 4 : 2;
+#ifdef _OPENMP
+    n_threads = omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int bj = 0; bj < B * n_q_heads; ++bj) {
+        int b = bj / n_q_heads, j = bj % n_q_heads, h = j / g;
+        int64_t bh = (int64_t)b * n_kv_heads + h;
+        int64_t n_kept = kept_off[bh + 1] - kept_off[bh];
+        double *qd = (double *)malloc(sizeof(double) * (size_t)d);
+        double *scratch = (double *)malloc(sizeof(double) * (size_t)(n_kept + n_new + 1));
+        for (int c = 0; c < d; ++c) qd[c] = widen(Q, dtype, (int64_t)bj * d + c);
+        const char *Kh = (const char *)K + (b * stride_b + h * stride_h) * esz;
+        const char *Vh = (const char *)V + (b * stride_b + h * stride_h) * esz;
+        const char *Kn = K_new ? (const char *)K_new + bh * cap_new * d * esz : NULL;
+        const char *Vn = V_new ? (const char *)V_new + bh * cap_new * d * esz : NULL;
+        oracle_attn_head(qd, d, scale, Kh, Vh, dtype, stride_n,
+                         kept + kept_off[bh], n_kept, Kn, Vn, d, n_new,
+                         khat + bh * d, vhat + bh * d, N_d[bh], scratch,
+                         out + (int64_t)bj * d);
+        free(qd);
+        free(scratch);
+    }
+    return n_threads;
+}
+
+/*
+ * Algorithm 1, steps 1-4 over a batch: selection and compensation tokens
+ * for every (sequence, KV head).  mask[h] != 0 marks a retrieval KV head
+ * (a model property, shared by all sequences).  kept must have room for
+ * sum_b n_kv_heads * seq_lens[b] entries; kept_off gets B*Hkv+1 entries.
+ */
+int oracle_compress_batch(const void *K, const void *V, int dtype,
+                          int B, int n_kv_heads, int d,
+                          int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                          const int64_t *seq_lens, const uint8_t *mask,
+                          int64_t n_sink, int64_t window,
+                          int64_t *kept, int64_t *kept_off,
+                          double *khat, double *vhat, int64_t *N_d)
+{
+    int n_threads = 1;
+    int64_t esz = dtype == ORACLE_F32 ? 4 : 2;
+    int64_t *d_lo = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B * n_kv_heads));
+    int64_t *d_hi = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B * n_kv_heads));
+    kept_off[0] = 0;
+    for (int bh = 0; bh < B * n_kv_heads; ++bh) {
+        int b = bh / n_kv_heads, h = bh % n_kv_heads;
+        int64_t n = oracle_select(seq_lens[b], mask[h] != 0, n_sink, window,
+                                  kept + kept_off[bh], &d_lo[bh], &d_hi[bh]);
+        kept_off[bh + 1] = kept_off[bh] + n;
+        N_d[bh] = d_hi[bh] - d_lo[bh];
+    }
+#ifdef _OPENMP
+    n_threads = omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int bh = 0; bh < B * n_kv_heads; ++bh) {
+        int b = bh / n_kv_heads, h = bh % n_kv_heads;
+        for (int c = 0; c < d; ++c) khat[(int64_t)bh * d + c] = vhat[(int64_t)bh * d + c] = 0.0;
+        if (N_d[bh] > 0) {
+            const char *Kh = (const char *)K + (b * stride_b + h * stride_h) * esz;
+            const char *Vh = (const char *)V + (b * stride_b + h * stride_h) * esz;
+            oracle_comp_token(Kh, Vh, dtype, stride_n, d, d_lo[bh], d_hi[bh],
+                              khat + (int64_t)bh * d, vhat + (int64_t)bh * d);
+        }
+    }
+    free(d_lo);
+    free(d_hi);
+    return n_threads;
+}
