@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Benchmark of the RazorAttention hot path on one MI355X.
+
+Workload (default): BASELINE config 3 -- a Llama-3-8B-shaped GQA layer, batch 4, 32 query
+heads over 8 KV heads, head_dim 128, context 131072, bf16, 2 of 8 KV heads retrieval,
+window max(4096, 15 % of context) + 4 sinks + compensation token.  Seeded synthetic data.
+
+A step is one razor_decode_attn call (append one token to every head, attend, combine) on
+a cache that razor_compress built before the timed region.  `value` is the algorithmic
+HBM bytes of a step divided by its wall time.  Also reported: the same kernel on the
+uncompressed cache (every head marked retrieval), the compression pass, the dominant
+kernel's own duration (HIP events around it on its stream) against the 8 TB/s roofline,
+and the fp64 CPU oracle timed on the host cores.
+
+Prints one JSON line.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes_decode(desc, p_d, esize, B, Hq, use_comp=True):
+    """Bytes a decode step has to move: every cached K and V row once, the fp32
+    compensation tokens, Q in and O out (fp32).  Split-K partials are overhead, not counted."""
+    rows = int(desc["rows"].astype("int64").sum())
+    n_comp = int((desc["n_dropped"] > 0).sum()) if use_comp else 0
+    return rows * 2 * p_d * esize + n_comp * 2 * p_d * 4 + B * Hq * p_d * esize + B * Hq * p_d * 4 \
+        + desc.size * 32
+
+
+def algorithmic_bytes_compress(desc, seq_lens, Hkv, p_d, esize):
+    """Read every valid source row once, write every kept row once, plus the compensation tokens."""
+    src_rows = int(seq_lens.astype("int64").sum()) * Hkv
+    kept = int(desc["rows"].astype("int64").sum())
+    return (src_rows + kept) * 2 * p_d * esize + desc.size * 2 * p_d * 4
+
+
+class HipEvents:
+    """Raw HIP events (torch.cuda.Event only sees torch's notion of the stream)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        assert rc == 0, f"hipEventCreate failed: {rc}"
+        return ev
+
+    def record(self, ev, stream):
+        assert self.hip.hipEventRecord(ev, ctypes.c_void_p(stream)) == 0
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        assert self.hip.hipEventSynchronize(b) == 0
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        assert rc == 0, f"hipEventElapsedTime failed: {rc}"
+        return ms.value
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4])
+    ap.add_argument("--copies", type=int, default=4, help="distinct caches rotated through, so the "
+                    "256 MB memory-side cache cannot serve a step's reads from the previous step")
+    ap.add_argument("--workers", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full", action="store_true", help="skip the uncompressed-cache comparison")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); the path shards by KV head "
+              "and batch with no exchange, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2407_15891_amd as razor
+    from paper_2407_15891_amd.workloads import make_workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    ev = HipEvents()
+
+    total_steps = args.steps + args.warmup
+    max_new = 2 * (total_steps // args.copies + 2)           # timed pass + kernel-timing pass
+    w = make_workload(args.config, dev, max_new=max_new)
+    esize = 4 if w.dtype == torch.float32 else 2
+    stream = torch.cuda.current_stream().cuda_stream
+    lib = razor.load_library()
+
+    def build_caches(mask, n):
+        caches = []
+        for _ in range(n):
+            c = razor.RazorCache(batch=w.B, n_q_heads=w.Hq, n_kv_heads=w.Hkv, head_dim=w.d,
+                                 seq_lens=w.seq_lens, retrieval_mask=mask, n_sink=w.n_sink,
+                                 window=w.window, max_new=max_new, dtype=w.dtype, scale=w.scale,
+                                 n_workers=args.workers, device=dev)
+            c.compress(w.K, w.V)
+            caches.append(c)
+        torch.cuda.synchronize()
+        return caches
+
+    # step inputs drawn ahead of the timed region (a handful, reused round-robin)
+    inputs = [w.step_inputs(t) for t in range(8)]
+    out = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=dev)
+
+    def run(caches, n, profile=False):
+        """n decode steps; returns (wall seconds, mean ms of the partial kernel or None)."""
+        pairs = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(n):
+            c = caches[t % len(caches)]
+            Q, k, v = inputs[t % len(inputs)]
+            if profile:
+                a, b = ev.create(), ev.create()
+                lib.razor_profile_events(a, b)
+                pairs.append((a, b))
+            c.decode(Q, k, v, out=out)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        if not profile:
+            return dt, None
+        lib.razor_profile_events(None, None)
+        ms = [ev.elapsed_ms(a, b) for a, b in pairs]
+        for a, b in pairs:
+            ev.hip.hipEventDestroy(a); ev.hip.hipEventDestroy(b)
+        return dt, float(np.mean(ms))
+
+    # ---------------- compressed cache
+    caches = build_caches(w.mask, args.copies)
+    desc0 = caches[0].desc()
+    run(caches, args.warmup)
+    wall, _ = run(caches, args.steps)
+    desc_mid = caches[0].desc()
+    _, kernel_ms = run(caches, args.steps, profile=True)
+    ms_per_step = wall / args.steps * 1e3
+    # rows grow by one per visit; take the table at the middle of the timed region
+    desc_avg = desc_mid.copy()
+    desc_avg["rows"] = (desc0["rows"] + args.warmup // args.copies + args.steps // (2 * args.copies))
+    step_bytes = algorithmic_bytes_decode(desc_avg, w.d, esize, w.B, w.Hq)
+    gbps = step_bytes / (wall / args.steps) / 1e9
+    kernel_gbps = step_bytes / (kernel_ms * 1e-3) / 1e9
+
+    # ---------------- compression pass (timed on its own: events around the call)
+    comp_bytes = algorithmic_bytes_compress(desc0, w.seq_lens, w.Hkv, w.d, esize)
+    a, b = ev.create(), ev.create()
+    reps = 5
+    caches[0].compress(w.K, w.V)
+    torch.cuda.synchronize()
+    ev.record(a, stream)
+    for r in range(reps):
+        caches[r % len(caches)].compress(w.K, w.V)
+    ev.record(b, stream)
+    compress_ms = ev.elapsed_ms(a, b) / reps
+    kept_rows = int(desc0["rows"].astype("int64").sum())
+    full_rows = int(w.seq_lens.astype("int64").sum()) * w.Hkv
+    del caches
+    torch.cuda.empty_cache()
+
+    # ---------------- the same kernels on the uncompressed cache
+    full = None
+    if not args.no_full:
+        fcaches = build_caches(np.ones(w.Hkv, np.uint8), max(2, args.copies // 2))
+        fdesc = fcaches[0].desc()
+        n_full = max(10, args.steps // 4)
+        run(fcaches, max(2, args.warmup // 4))
+        fwall, _ = run(fcaches, n_full)
+        _, fkernel_ms = run(fcaches, n_full, profile=True)
+        fbytes = algorithmic_bytes_decode(fdesc, w.d, esize, w.B, w.Hq)
+        full = {"ms_per_step": fwall / n_full * 1e3, "GBps": fbytes / (fwall / n_full) / 1e9,
+                "kernel_ms": fkernel_ms, "kernel_GBps": fbytes / (fkernel_ms * 1e-3) / 1e9,
+                "bytes": fbytes, "steps": n_full}
+        del fcaches
+        torch.cuda.empty_cache()
+
+    # ---------------- CPU oracle on the host cores (reported baseline, not the target)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import razor_oracle as orc
+        nb = 1                                               # sample: sequence 0 of the batch
+        Kc, Vc = w.K[:nb].cpu(), w.V[:nb].cpu()
+        oc = orc.OracleCache(Kc, Vc, w.seq_lens[:nb], w.mask, w.n_sink, w.window, max_new=1)
+        Q, k, v = inputs[0]
+        oc.append(k[:nb].cpu(), v[:nb].cpu())
+        Qc = Q[:nb].cpu()
+        best = float("inf")
+        for _ in range(2):
+            t0 = time.perf_counter()
+            oc.decode(Qc, w.scale)
+            best = min(best, time.perf_counter() - t0)
+        d_s = desc0[: nb * w.Hkv].copy()
+        d_s["rows"] += 1
+        sample_bytes = algorithmic_bytes_decode(d_s, w.d, esize, nb, w.Hq)
+        cpu = {"value": sample_bytes / best / 1e9, "unit": "GB/s", "cores": int(oc.threads),
+               "kind": "oracle", "seconds": best,
+               "sample": f"one decode step of sequence 0 of {w.B} (all {w.Hkv} KV heads, "
+                         f"{int(d_s['rows'].sum())} cached rows), fp64 C + OpenMP oracle, best of 2"}
+
+    result = {
+        "metric": "compressed decode-attention HBM GB/s (% of peak) + speedup vs full cache, 128K",
+        "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": f"BASELINE config {args.config}: {w.name}, batch {w.B}, {w.Hq} query / "
+                               f"{w.Hkv} KV heads, head_dim {w.d}, context {w.N}, window {w.window}, "
+                               f"{w.n_sink} sinks, {int(w.mask.sum())} retrieval KV heads; one step = "
+                               "append one token + compressed decode attention + combine",
+                   "cached_rows": kept_rows, "full_rows": full_rows, "copies_rotated": args.copies},
+        "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
+        "step_bytes": step_bytes,
+        "byte_ratio_full_over_compressed": (full["bytes"] / step_bytes) if full else full_rows / kept_rows,
+        "speedup_vs_full_cache": (full["ms_per_step"] / ms_per_step) if full else None,
+        "full_cache": full,
+        "compress": {"ms": compress_ms, "bytes": comp_bytes, "GBps": comp_bytes / (compress_ms * 1e-3) / 1e9,
+                     "pct_of_hbm_peak": 100.0 * comp_bytes / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "roofline": {"bound": "hbm", "kernel": "decode_partial (streams K/V, online softmax)",
+                     "achieved": kernel_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": kernel_gbps / HBM_PEAK_GBPS, "kernel_ms": kernel_ms, "traffic": None},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

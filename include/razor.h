@@ -1,0 +1,168 @@
+/*
+ * razor.h -- C ABI of the RazorAttention hot path for AMD MI355X (gfx950).
+ *
+ * Two device operations and one host-only planner:
+ *
+ *   razor_plan         Algorithm 1, steps 2-3 as integer arithmetic: which rows
+ *                      every (sequence, KV head) keeps, and where they live.
+ *   razor_compress     Algorithm 1, steps 1-4: builds the per-head heterogeneous
+ *                      cache from a full post-RoPE K/V cache -- retrieval heads
+ *                      keep every row; the others keep n_sink leading rows, the
+ *                      last `window` rows and one compensation token, the mean
+ *                      of the dropped keys / values (Eq.(4)).
+ *   razor_decode_attn  Algorithm 1, step 5: one query per sequence attends the
+ *                      compressed cache; the compensation token enters the
+ *                      softmax with multiplicity N_d exactly as in Eq.(5).
+ *
+ * Conventions
+ *   - Pointers are DEVICE pointers unless their name ends in _host.
+ *   - The library owns no memory and keeps no state between calls.  The caller
+ *     allocates every buffer with the sizes razor_plan reports.  Device calls
+ *     only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream); they never allocate, never synchronise.
+ *   - All functions return RAZOR_OK (0) or a negative razor_status.  Arguments
+ *     are validated on the host before anything is enqueued; a failing call
+ *     enqueues nothing.
+ *   - One call handles one transformer layer.  The retrieval mask is a model
+ *     property: one byte per KV head, shared by every sequence of the batch.
+ *     Under GQA a KV head is retrieval if any query head of its group is
+ *     (Sec. 4.1 of the paper); that OR is taken by the caller.
+ *   - K, V, Q are expected after the rotary transform (Algorithm 1 input); the
+ *     library never applies positions.
+ *
+ * Cache layout (opaque to callers except through razor_head_desc)
+ *   arena   per (b, kv head): a K plane of `cap` rows followed by a V plane of
+ *           `cap` rows, head_dim elements per row, starting at element offset
+ *           row_off * 2 * head_dim.  `cap` is a multiple of 16.  V rows are
+ *           stored row-major.  K rows are stored in blocks of 16 rows; inside a
+ *           block the 16-byte piece c of row r sits at byte (c * 16 + r) * 16,
+ *           so that one wavefront-wide 128-bit load yields a matrix-core
+ *           operand without a transpose.
+ *   comp    float32 [batch, n_kv_heads, 2, head_dim]: khat then vhat of Eq.(4)
+ *           (zeros for heads that dropped nothing).
+ *   desc    razor_head_desc[batch * n_kv_heads], index b * n_kv_heads + h.
+ */
+#ifndef RAZOR_H
+#define RAZOR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum razor_dtype { RAZOR_F32 = 0, RAZOR_BF16 = 1 } razor_dtype;
+
+typedef enum razor_status {
+    RAZOR_OK = 0,
+    RAZOR_EINVAL = -1,     /* null pointer, unsupported dtype / head_dim / group size, bad length or stride */
+    RAZOR_ECAPACITY = -2,  /* workspace smaller than razor_plan asked for */
+    RAZOR_EHIP = -3        /* a HIP runtime call failed (razor_strerror gives its text) */
+} razor_status;
+
+/* flags of razor_head_desc */
+#define RAZOR_HEAD_RETRIEVAL 1u /* mask bit was set: full cache kept                          */
+#define RAZOR_HEAD_COMP 2u      /* rows were dropped: comp[] holds a compensation token        */
+#define RAZOR_HEAD_OVERFLOW 4u  /* a decode append found the head full and was not stored      */
+
+#define RAZOR_BLOCK_ROWS 16    /* K rows per arena block                                       */
+#define RAZOR_MAX_GROUP 16     /* largest n_q_heads / n_kv_heads                               */
+#define RAZOR_MAX_WORKERS 8192 /* upper bound on wavefronts a decode launch splits the cache over */
+
+typedef struct razor_params {
+    int32_t batch;       /* B >= 1 */
+    int32_t n_q_heads;   /* H_q, multiple of n_kv_heads, group size <= RAZOR_MAX_GROUP */
+    int32_t n_kv_heads;  /* H_kv */
+    int32_t head_dim;    /* 64 or 128 */
+    int32_t n_sink;      /* N_0 of Algorithm 1 (Table 2 uses 4), >= 0 */
+    int32_t window;      /* buffer length L_h = max(S_0, N / C) already evaluated by the caller, >= 0 */
+    int32_t max_new;     /* rows reserved per head for decode-time appends, >= 0 */
+    int32_t use_comp;    /* 1: Eq.(5).  0: drop the compensation term (sinks + window only) */
+    int32_t dtype;       /* razor_dtype of Q, K, V, k_new, v_new and of the arena */
+    int32_t out_dtype;   /* razor_dtype of O */
+    float scale;         /* multiplies every logit, the compensation logit included; 1.0f is
+                            Eq.(5) as printed, 1/sqrt(head_dim) what the evaluated models use */
+    int32_t n_workers;   /* wavefronts to split a decode over; 0 = pick from the device */
+} razor_params;
+
+/* One entry per (sequence b, KV head h).  Written by razor_plan (host copy) and
+ * razor_compress (device copy); `rows` and the overflow flag of the device copy
+ * are updated by razor_decode_attn when it appends. */
+typedef struct razor_head_desc {
+    int64_t row_off;   /* first row of this head's region, in rows of 2*head_dim elements */
+    int64_t kept_off;  /* first entry of this head in kept_idx                             */
+    int32_t rows;      /* cached rows (compensation token not counted)                     */
+    int32_t cap;       /* rows reserved; multiple of 16, >= rows at plan time + max_new   */
+    int32_t n_dropped; /* N_d of Eq.(4)/(5); 0 when nothing was dropped                    */
+    uint32_t flags;    /* RAZOR_HEAD_*                                                     */
+} razor_head_desc;
+
+typedef struct razor_sizes {
+    uint64_t arena_bytes;
+    uint64_t comp_bytes;
+    uint64_t desc_bytes;
+    uint64_t kept_idx_bytes;
+    uint64_t workspace_bytes; /* enough for razor_compress and for razor_decode_attn */
+    int64_t total_rows;       /* sum of rows over all heads */
+    int64_t total_cap;        /* sum of cap over all heads  */
+} razor_sizes;
+
+/*
+ * Host-only; touches no GPU.  Algorithm 1 steps 2-3 for every (b, h):
+ *   retrieval head, or seq_len <= n_sink + window:  keep rows [0, seq_len), N_d = 0;
+ *   otherwise keep [0, n_sink) and [seq_len - window, seq_len), N_d = seq_len - n_sink - window.
+ * seq_lens_host[batch] (each >= 1), retrieval_mask_host[n_kv_heads] (non-zero = retrieval).
+ * desc_host[batch * n_kv_heads] and kept_idx_host[total_rows] may each be NULL (sizes only;
+ * kept positions ascending per head, heads in desc order).  sizes must not be NULL.
+ */
+int razor_plan(const razor_params *p, const int32_t *seq_lens_host,
+               const uint8_t *retrieval_mask_host, razor_head_desc *desc_host,
+               int32_t *kept_idx_host, razor_sizes *sizes);
+
+/*
+ * Builds arena, comp and desc_dev from the full cache (Eq.(4) + Algorithm 1 step 3).
+ * K, V: element [b, h, n, c] at b*stride_b + h*stride_h + n*stride_n + c (strides in
+ * elements, last dimension contiguous, 16-byte aligned rows); rows n >= seq_lens[b] are
+ * never read.  kept_idx_dev (int32[total_rows], nullable) receives the kept positions.
+ * After the call the arena is self-contained: the caller may release K and V.
+ * Means are accumulated in fp32 in a fixed order (bit-reproducible run to run).
+ */
+int razor_compress(const razor_params *p, const void *K, const void *V,
+                   int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                   const int32_t *seq_lens_host, const uint8_t *retrieval_mask_host,
+                   void *arena, float *comp, razor_head_desc *desc_dev,
+                   int32_t *kept_idx_dev, void *workspace, size_t workspace_bytes,
+                   void *stream);
+
+/*
+ * One decode step.  If k_new and v_new ([batch, n_kv_heads, head_dim]) are non-NULL the
+ * new token is first appended to every head (rows += 1; a full head sets
+ * RAZOR_HEAD_OVERFLOW and skips the append), then Q [batch, n_q_heads, head_dim] attends:
+ * retrieval heads by plain softmax attention, the others by Eq.(5), logits scaled by
+ * p->scale, accumulation in fp32.  O [batch, n_q_heads, head_dim] in p->out_dtype.
+ * p must describe the same batch / heads / head_dim / dtype the cache was built with.
+ * Results are bit-reproducible run to run (no floating-point atomics).
+ */
+int razor_decode_attn(const razor_params *p, const void *Q, const void *k_new,
+                      const void *v_new, void *arena, const float *comp,
+                      razor_head_desc *desc_dev, void *O, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/*
+ * Measurement hook.  After this call, every razor_decode_attn issued by the calling
+ * thread records ev_start (a hipEvent_t) on its stream right before the kernel that
+ * streams the cache and ev_stop right after it, so a benchmark can time that kernel
+ * alone.  Pass NULL, NULL to switch the hook off (the default).  The events stay owned
+ * by the caller.  Always returns RAZOR_OK.
+ */
+int razor_profile_events(void *ev_start, void *ev_stop);
+
+/* Text for a razor_status; for RAZOR_EHIP the text of the last HIP error seen by the
+ * calling thread.  The pointer stays valid until the thread's next failing call. */
+const char *razor_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAZOR_H */

@@ -1,0 +1,624 @@
+// razor_decode_attn: one decode step over the per-head heterogeneous cache
+// (Algorithm 1 step 5, Eq.(5)).  Three launches on the caller's stream:
+//
+//   prepare   appends the new token to every head and writes, per head, the prefix
+//             sum of its 16-row block count -- the ragged length table flattened
+//             into one block axis.
+//   partial   the flattened block axis is cut into equal ranges, one per wavefront.
+//             A wavefront streams the K and V blocks of its range once from HBM with
+//             128-bit loads held in registers several blocks ahead, keeps an online
+//             softmax state (running max, denominator, unnormalised output) for the
+//             whole query group of the KV head, and stores one partial state per
+//             head segment it touched.  Long retrieval heads and short compressed
+//             heads therefore cost exactly their bytes; no wavefront idles behind
+//             another, and waves never synchronise with each other.
+//   combine   merges the partial states of each query head in a fixed order, folds
+//             in the compensation token with weight N_d (logit + ln N_d), normalises.
+//
+// bf16 caches use the matrix cores for both products (the query group is padded to
+// the 16-wide operand); fp32 caches use vector FMAs.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <type_traits>
+
+#include "razor_internal.h"
+
+namespace razor {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kNegInf = -__builtin_huge_valf();
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Rows a head holds during this step: the stored count plus the token being appended
+// (an append to a full head is skipped everywhere by the same test).
+__device__ __forceinline__ int rows_this_step(const razor_head_desc &e, int has_new)
+{
+    return e.rows + ((has_new && e.rows < e.cap) ? 1 : 0);
+}
+
+// ---------------------------------------------------------------- prepare
+template <int RB>
+__global__ __launch_bounds__(64) void prepare_kernel(
+    const razor_head_desc *__restrict__ desc, const char *__restrict__ k_new,
+    const char *__restrict__ v_new, char *__restrict__ arena, int n_heads, int n_workers,
+    int32_t *__restrict__ prefix)
+{
+    constexpr int LPR = RB / 16;
+    const int lane = threadIdx.x;
+    if ((int)blockIdx.x < n_heads) {           // append one row to head blockIdx.x
+        if (!k_new) return;
+        const razor_head_desc e = desc[blockIdx.x];
+        if (e.rows >= e.cap) return;
+        const int t = e.rows;
+        char *kplane = arena + e.row_off * 2 * RB;
+        char *vplane = kplane + (int64_t)e.cap * RB;
+        if (lane < LPR) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(k_new + (int64_t)blockIdx.x * RB + lane * 16);
+            char *blk = kplane + (int64_t)(t / kBlockRows) * kBlockRows * RB;
+            *reinterpret_cast<uint4 *>(blk + (lane * 16 + t % kBlockRows) * 16) = v;
+        } else if (lane >= 32 && lane < 32 + LPR) {
+            const int piece = lane - 32;
+            const uint4 v = *reinterpret_cast<const uint4 *>(v_new + (int64_t)blockIdx.x * RB + piece * 16);
+            *reinterpret_cast<uint4 *>(vplane + (int64_t)t * RB + piece * 16) = v;
+        }
+        return;
+    }
+    // last workgroup: prefix sums of the block counts
+    int carry = 0;
+    for (int base = 0; base < n_heads; base += 64) {
+        const int idx = base + lane;
+        int incl = 0;
+        if (idx < n_heads)
+            incl = (rows_this_step(desc[idx], k_new != nullptr) + kBlockRows - 1) / kBlockRows;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
+        }
+        if (idx < n_heads) prefix[idx + 1] = carry + incl;
+        carry += __shfl(incl, 63);
+    }
+    if (lane == 0) {
+        prefix[0] = 0;
+        int per = (carry + n_workers - 1) / n_workers;
+        prefix[n_heads + 1] = per < kMinBlocksPerWorker ? kMinBlocksPerWorker : per;
+    }
+}
+
+// Index of the head that owns flattened block `blk` (wave-uniform).
+__device__ __forceinline__ int find_head(const int32_t *__restrict__ prefix, int n_heads, int blk,
+                                         int lane)
+{
+    int count = 0;
+    for (int base = 0; base < n_heads; base += 64) {
+        const int idx = base + lane;
+        const bool ended = idx < n_heads && prefix[idx + 1] <= blk;
+        const int c = __popcll(__ballot(ended));
+        count += c;
+        if (c < 64) break;
+    }
+    return count;
+}
+
+// ---------------------------------------------------------------- partial, bf16 / matrix cores
+//
+// Lane l = 16 * kg + n.  For one 16-row block:
+//   S[row][head]  = K[row][:] . Q[head][:]    v_mfma_f32_16x16x32_bf16, A = K block, B = Q
+//                   lane (kg, n) ends up with head n, rows 4*kg .. 4*kg+3
+//   P             = exp2(S - max), rounded to bf16, still in those lanes: it is already
+//                   the B operand of the second product
+//   O^T[col][head] += V^T[col][row] . P[row][head]   v_mfma_f32_16x16x16_bf16, A = V^T
+//                   lane (kg, n) loads 16 bytes of rows 4*kg .. 4*kg+3 (coalesced), and a
+//                   4-row in-lane transpose (v_perm_b32) yields A for one column phase e
+//                   lane (kg, n) accumulates head n, columns 4*VE*kg .. 4*VE*kg + 4*VE-1
+// The K plane is stored piece-major per block, so the A operand of the first product is
+// one contiguous 1 KB load per 32 columns.  The denominator sums the bf16-rounded P, the
+// same numbers the matrix core multiplies, so numerator and denominator stay consistent.
+template <int D, int PF>
+__global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
+    const uint16_t *__restrict__ Q, const char *__restrict__ arena,
+    const razor_head_desc *__restrict__ desc, const int32_t *__restrict__ prefix,
+    float *__restrict__ part_ml, float *__restrict__ part_acc, int n_heads, int n_kv_heads, int g,
+    int has_new, float scale_log2e)
+{
+    constexpr int RB = D * 2;     // bytes per row
+    constexpr int NS = D / 32;    // K loads (= first-product steps) per block
+    constexpr int VE = D / 16;    // V elements per lane per row
+    using VT = typename std::conditional<VE == 8, uint4, uint2>::type;
+
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int kg = lane >> 4, n = lane & 15;
+    const int per = prefix[n_heads + 1], total = prefix[n_heads];
+    int lo = w * per;
+    const int hi = lo + per < total ? lo + per : total;
+    if (lo >= hi) return;
+    int i = find_head(prefix, n_heads, lo, lane);
+
+    while (lo < hi) {
+        while (prefix[i + 1] <= lo) ++i;
+        const int first = prefix[i];
+        const int seg_end = hi < prefix[i + 1] ? hi : prefix[i + 1];
+        const razor_head_desc e = desc[i];
+        const int rows = rows_this_step(e, has_new);
+        const int b = i / n_kv_heads, h = i % n_kv_heads;
+        const char *kplane = arena + e.row_off * 2 * RB;
+        const char *vplane = kplane + (int64_t)e.cap * RB;
+
+        bf16x8 qreg[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            uint4 qv = make_uint4(0, 0, 0, 0);
+            if (n < g)
+                qv = *reinterpret_cast<const uint4 *>(
+                    Q + ((int64_t)(b * n_kv_heads + h) * g + n) * D + (4 * s + kg) * 8);
+            qreg[s] = __builtin_bit_cast(bf16x8, qv);
+        }
+
+        float m = kNegInf, l = 0.f;
+        f32x4 acc[VE];
+#pragma unroll
+        for (int c = 0; c < VE; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        uint4 kb[PF][NS];
+        VT vb[PF][4];
+        auto load_block = [&](int t, uint4(&k)[NS], VT(&v)[4]) {
+            const uint4 *kp = reinterpret_cast<const uint4 *>(kplane + (int64_t)t * kBlockRows * RB) + lane;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) k[s] = kp[s * 64];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                int row = t * kBlockRows + 4 * kg + r;
+                row = row < rows ? row : rows - 1;   // stay on initialised, finite rows
+                v[r] = *(reinterpret_cast<const VT *>(vplane + (int64_t)row * RB) + n);
+            }
+        };
+        auto compute_block = [&](int t, const uint4(&k)[NS], const VT(&v)[4]) {
+            f32x4 S = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k[s]), qreg[s], S, 0, 0, 0);
+            float sv[4];
+            const int row0 = t * kBlockRows + 4 * kg;
+            float bmax = kNegInf;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                sv[r] = row0 + r < rows ? S[r] * scale_log2e : kNegInf;
+                bmax = fmaxf(bmax, sv[r]);
+            }
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+            const float m_new = fmaxf(m, bmax);     // finite: every block holds a valid row
+            const float alpha = fast_exp2(m - m_new);
+            m = m_new;
+            s16x4 pk;
+            float psum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const __bf16 pb = (__bf16)fast_exp2(sv[r] - m_new);
+                psum += (float)pb;
+                pk[r] = __builtin_bit_cast(short, pb);
+            }
+            l = l * alpha + psum;
+#pragma unroll
+            for (int c = 0; c < VE; ++c) {
+                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+                const uint32_t w0 = reinterpret_cast<const uint32_t *>(&v[0])[c >> 1];
+                const uint32_t w1 = reinterpret_cast<const uint32_t *>(&v[1])[c >> 1];
+                const uint32_t w2 = reinterpret_cast<const uint32_t *>(&v[2])[c >> 1];
+                const uint32_t w3 = reinterpret_cast<const uint32_t *>(&v[3])[c >> 1];
+                uint2 packed;
+                packed.x = __builtin_amdgcn_perm(w1, w0, sel);   // rows 4kg, 4kg+1 of column phase c
+                packed.y = __builtin_amdgcn_perm(w3, w2, sel);   // rows 4kg+2, 4kg+3
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+                    __builtin_bit_cast(s16x4, packed), pk, acc[c] * alpha, 0, 0, 0);
+            }
+        };
+
+        const int t0 = lo - first, t1 = seg_end - first;
+#pragma unroll
+        for (int u = 0; u < PF; ++u)
+            if (t0 + u < t1) load_block(t0 + u, kb[u], vb[u]);
+        for (int t = t0; t < t1; t += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                if (t + u < t1) {
+                    compute_block(t + u, kb[u], vb[u]);
+                    if (t + u + PF < t1) load_block(t + u + PF, kb[u], vb[u]);
+                }
+            }
+        }
+
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (n < g) {
+            const size_t slot = (size_t)(w + i) * g + n;
+            float *pa = part_acc + slot * D + 4 * VE * kg;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < VE; c += 4)
+                    *reinterpret_cast<float4 *>(pa + VE * r + c) =
+                        make_float4(acc[c][r], acc[c + 1][r], acc[c + 2][r], acc[c + 3][r]);
+            if (kg == 0) {
+                part_ml[slot * 2] = m;
+                part_ml[slot * 2 + 1] = l;
+            }
+        }
+        lo = seg_end;
+    }
+}
+
+// ---------------------------------------------------------------- partial, fp32 / vector ALU
+//
+// Lane l = 16 * kg + n holds, per K load s, the 4 floats of piece 4*s + kg of row n; the
+// dot product is finished across the four kg groups with two shuffles.  V is read
+// row-major: lane (prow, piece) holds 4 columns of row i*RPI + prow and picks that row's
+// probability from the lane that owns it.
+template <int D, int G, int PF>
+__global__ __launch_bounds__(256) void decode_partial_f32_kernel(
+    const float *__restrict__ Q, const char *__restrict__ arena,
+    const razor_head_desc *__restrict__ desc, const int32_t *__restrict__ prefix,
+    float *__restrict__ part_ml, float *__restrict__ part_acc, int n_heads, int n_kv_heads, int g,
+    int has_new, float scale_log2e)
+{
+    constexpr int RB = D * 4;
+    constexpr int NS = RB / 64;     // K loads per block
+    constexpr int LPR = RB / 16;    // lanes per V row
+    constexpr int RPI = 64 / LPR;   // V rows per load
+    constexpr int NI = 16 / RPI;    // V loads per block
+    __shared__ float qs[4][G * D];  // the query group, private to each wave
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + wave;
+    const int kg = lane >> 4, n = lane & 15;
+    const int prow = lane / LPR, piece = lane % LPR;
+    const int per = prefix[n_heads + 1], total = prefix[n_heads];
+    int lo = w * per;
+    const int hi = lo + per < total ? lo + per : total;
+    if (lo >= hi) return;
+    int i = find_head(prefix, n_heads, lo, lane);
+
+    while (lo < hi) {
+        while (prefix[i + 1] <= lo) ++i;
+        const int first = prefix[i];
+        const int seg_end = hi < prefix[i + 1] ? hi : prefix[i + 1];
+        const razor_head_desc e = desc[i];
+        const int rows = rows_this_step(e, has_new);
+        const int b = i / n_kv_heads, h = i % n_kv_heads;
+        const char *kplane = arena + e.row_off * 2 * RB;
+        const char *vplane = kplane + (int64_t)e.cap * RB;
+
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (int t = lane; t < G * D; t += 64)
+            qs[wave][t] = t < g * D ? Q[(int64_t)(b * n_kv_heads + h) * g * D + t] : 0.f;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        float m[G], l[G];
+        float4 acc[G];
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            m[j] = kNegInf;
+            l[j] = 0.f;
+            acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+
+        float4 kb[PF][NS], vb[PF][NI];
+        auto load_block = [&](int t, float4(&k)[NS], float4(&v)[NI]) {
+            const float4 *kp = reinterpret_cast<const float4 *>(kplane + (int64_t)t * kBlockRows * RB) + lane;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) k[s] = kp[s * 64];
+#pragma unroll
+            for (int r = 0; r < NI; ++r) {
+                int row = t * kBlockRows + r * RPI + prow;
+                row = row < rows ? row : rows - 1;
+                v[r] = *(reinterpret_cast<const float4 *>(vplane + (int64_t)row * RB) + piece);
+            }
+        };
+        auto compute_block = [&](int t, const float4(&k)[NS], const float4(&v)[NI]) {
+            const bool valid = t * kBlockRows + n < rows;
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                if (j < g) {
+                    float dot = 0.f;
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) {
+                        const float4 q4 = *reinterpret_cast<const float4 *>(&qs[wave][j * D + 4 * (4 * s + kg)]);
+                        dot += k[s].x * q4.x + k[s].y * q4.y + k[s].z * q4.z + k[s].w * q4.w;
+                    }
+                    dot += __shfl_xor(dot, 16);
+                    dot += __shfl_xor(dot, 32);
+                    const float sv = valid ? dot * scale_log2e : kNegInf;
+                    float bmax = sv;
+                    bmax = fmaxf(bmax, __shfl_xor(bmax, 1));
+                    bmax = fmaxf(bmax, __shfl_xor(bmax, 2));
+                    bmax = fmaxf(bmax, __shfl_xor(bmax, 4));
+                    bmax = fmaxf(bmax, __shfl_xor(bmax, 8));
+                    const float m_new = fmaxf(m[j], bmax);
+                    const float alpha = fast_exp2(m[j] - m_new);
+                    m[j] = m_new;
+                    const float p = fast_exp2(sv - m_new);
+                    l[j] = l[j] * alpha + p;
+                    float4 a = acc[j];
+                    a.x *= alpha; a.y *= alpha; a.z *= alpha; a.w *= alpha;
+#pragma unroll
+                    for (int r = 0; r < NI; ++r) {
+                        const float pv = __shfl(p, r * RPI + prow);
+                        a.x += pv * v[r].x; a.y += pv * v[r].y; a.z += pv * v[r].z; a.w += pv * v[r].w;
+                    }
+                    acc[j] = a;
+                }
+            }
+        };
+
+        const int t0 = lo - first, t1 = seg_end - first;
+#pragma unroll
+        for (int u = 0; u < PF; ++u)
+            if (t0 + u < t1) load_block(t0 + u, kb[u], vb[u]);
+        for (int t = t0; t < t1; t += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                if (t + u < t1) {
+                    compute_block(t + u, kb[u], vb[u]);
+                    if (t + u + PF < t1) load_block(t + u + PF, kb[u], vb[u]);
+                }
+            }
+        }
+
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            if (j < g) {
+                float lt = l[j];   // one copy per row lives in each kg group: add over n only
+                lt += __shfl_xor(lt, 1);
+                lt += __shfl_xor(lt, 2);
+                lt += __shfl_xor(lt, 4);
+                lt += __shfl_xor(lt, 8);
+                float4 a = acc[j];
+#pragma unroll
+                for (int o = LPR; o < 64; o <<= 1) {
+                    a.x += __shfl_xor(a.x, o);
+                    a.y += __shfl_xor(a.y, o);
+                    a.z += __shfl_xor(a.z, o);
+                    a.w += __shfl_xor(a.w, o);
+                }
+                const size_t slot = (size_t)(w + i) * g + j;
+                if (prow == 0) *reinterpret_cast<float4 *>(part_acc + slot * D + 4 * piece) = a;
+                if (lane == 0) {
+                    part_ml[slot * 2] = m[j];
+                    part_ml[slot * 2 + 1] = lt;
+                }
+            }
+        }
+        lo = seg_end;
+    }
+}
+
+// ---------------------------------------------------------------- combine
+__device__ __forceinline__ float load_q(const void *Q, int dtype, int64_t idx)
+{
+    if (dtype == RAZOR_F32) return static_cast<const float *>(Q)[idx];
+    return __uint_as_float((uint32_t) static_cast<const uint16_t *>(Q)[idx] << 16);
+}
+
+// One workgroup per query head.  Eq.(5): the compensation token is one more softmax
+// entry with logit scale * q.khat + ln N_d and value vhat; the partial states of the
+// head's segments are merged around the common maximum in slot order.
+template <int D>
+__global__ __launch_bounds__(256) void combine_kernel(
+    const void *__restrict__ Q, int q_dtype, const float *__restrict__ comp,
+    razor_head_desc *__restrict__ desc, const int32_t *__restrict__ prefix,
+    const float *__restrict__ part_ml, const float *__restrict__ part_acc, void *__restrict__ O,
+    int out_dtype, int n_heads, int n_kv_heads, int g, int has_new, int use_comp, float scale_log2e)
+{
+    constexpr int C4 = D / 4;        // float4 columns
+    constexpr int GR = 256 / C4;     // slot groups working in parallel
+    __shared__ float red[256];
+    __shared__ float4 red4[GR][C4];
+    __shared__ float redl[GR];
+    const int tid = threadIdx.x;
+    const int n_q_heads = n_kv_heads * g;
+    const int bj = blockIdx.x, b = bj / n_q_heads, j = bj % n_q_heads;
+    const int h = j / g, n = j % g, i = b * n_kv_heads + h;
+    const razor_head_desc e = desc[i];
+    const int per = prefix[n_heads + 1];
+    const int first = prefix[i], last = prefix[i + 1];
+    const int w0 = first / per;
+    const int n_slots = last > first ? (last - 1) / per - w0 + 1 : 0;
+    const bool has_comp = use_comp && e.n_dropped > 0;
+
+    float part = 0.f;
+    if (has_comp && tid < D) part = load_q(Q, q_dtype, (int64_t)bj * D + tid) * comp[(size_t)i * 2 * D + tid];
+    red[tid] = part;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    const float m_comp = has_comp ? red[0] * scale_log2e + log2f((float)e.n_dropped) : kNegInf;
+    __syncthreads();
+
+    float mx = m_comp;
+    for (int s = tid; s < n_slots; s += 256)
+        mx = fmaxf(mx, part_ml[((size_t)(w0 + s + i) * g + n) * 2]);
+    red[tid] = mx;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] = fmaxf(red[tid], red[tid + o]);
+        __syncthreads();
+    }
+    const float M = red[0];
+
+    const int col = tid % C4, grp = tid / C4;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lsum = 0.f;
+    for (int s = grp; s < n_slots; s += GR) {
+        const size_t slot = (size_t)(w0 + s + i) * g + n;
+        const float wgt = fast_exp2(part_ml[slot * 2] - M);
+        const float4 v = *reinterpret_cast<const float4 *>(part_acc + slot * D + 4 * col);
+        a.x += wgt * v.x; a.y += wgt * v.y; a.z += wgt * v.z; a.w += wgt * v.w;
+        lsum += wgt * part_ml[slot * 2 + 1];
+    }
+    if (grp == 0 && has_comp) {
+        const float wgt = fast_exp2(m_comp - M);
+        const float4 v = *reinterpret_cast<const float4 *>(comp + ((size_t)i * 2 + 1) * D + 4 * col);
+        a.x += wgt * v.x; a.y += wgt * v.y; a.z += wgt * v.z; a.w += wgt * v.w;
+        lsum += wgt;
+    }
+    red4[grp][col] = a;
+    if (col == 0) redl[grp] = lsum;
+    __syncthreads();
+    if (grp == 0) {
+        float den = 0.f;
+        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < GR; ++k) {
+            const float4 v = red4[k][col];
+            num.x += v.x; num.y += v.y; num.z += v.z; num.w += v.w;
+            den += redl[k];
+        }
+        const float inv = den > 0.f ? 1.f / den : 0.f;   // a head with no entry at all gives zeros
+        num.x *= inv; num.y *= inv; num.z *= inv; num.w *= inv;
+        if (out_dtype == RAZOR_F32) {
+            *reinterpret_cast<float4 *>(static_cast<float *>(O) + (int64_t)bj * D + 4 * col) = num;
+        } else {
+            const __bf16 o0 = (__bf16)num.x, o1 = (__bf16)num.y, o2 = (__bf16)num.z, o3 = (__bf16)num.w;
+            uint2 pk;
+            pk.x = (uint32_t)__builtin_bit_cast(uint16_t, o0) | ((uint32_t)__builtin_bit_cast(uint16_t, o1) << 16);
+            pk.y = (uint32_t)__builtin_bit_cast(uint16_t, o2) | ((uint32_t)__builtin_bit_cast(uint16_t, o3) << 16);
+            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(O) + (int64_t)bj * D + 4 * col) = pk;
+        }
+    }
+    // the step is over for this head: make the appended row permanent
+    if (has_new && n == 0 && tid == 0) {
+        if (e.rows < e.cap) desc[i].rows = e.rows + 1;
+        else desc[i].flags = e.flags | RAZOR_HEAD_OVERFLOW;
+    }
+}
+
+#define RAZOR_HIP_CHECK(expr)                                              \
+    do {                                                                   \
+        hipError_t err__ = (expr);                                         \
+        if (err__ != hipSuccess) return hip_failure(#expr, (int)err__);    \
+    } while (0)
+
+thread_local hipEvent_t g_profile_start = nullptr, g_profile_stop = nullptr;
+
+int auto_workers(int *out)
+{
+    static thread_local int cached_dev = -1, cached = 0;
+    int dev = 0;
+    RAZOR_HIP_CHECK(hipGetDevice(&dev));
+    if (dev != cached_dev) {
+        int cus = 0;
+        RAZOR_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        cached = std::min(RAZOR_MAX_WORKERS, cus * 8);   // two 4-wave workgroups per compute unit
+        cached_dev = dev;
+    }
+    *out = cached;
+    return RAZOR_OK;
+}
+
+template <int G>
+void launch_partial_f32(int D, dim3 grid, hipStream_t s, const float *Q, const char *arena,
+                        const razor_head_desc *desc, const int32_t *prefix, float *ml, float *acc,
+                        int n_heads, int n_kv, int g, int has_new, float sl2e)
+{
+    if (D == 64)
+        hipLaunchKernelGGL((decode_partial_f32_kernel<64, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
+                           prefix, ml, acc, n_heads, n_kv, g, has_new, sl2e);
+    else
+        hipLaunchKernelGGL((decode_partial_f32_kernel<128, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
+                           prefix, ml, acc, n_heads, n_kv, g, has_new, sl2e);
+}
+
+}  // namespace
+}  // namespace razor
+
+extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const void *k_new,
+                                 const void *v_new, void *arena, const float *comp,
+                                 razor_head_desc *desc_dev, void *O, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    using namespace razor;
+    if (check_params(p) != RAZOR_OK) return RAZOR_EINVAL;
+    if (!Q || !arena || !comp || !desc_dev || !O || !workspace) return RAZOR_EINVAL;
+    if ((k_new == nullptr) != (v_new == nullptr)) return RAZOR_EINVAL;
+    if (((uintptr_t)Q | (uintptr_t)arena | (uintptr_t)comp | (uintptr_t)O | (uintptr_t)workspace |
+         (uintptr_t)k_new | (uintptr_t)v_new) & 15)
+        return RAZOR_EINVAL;
+    const DecodeWorkspace ws = decode_workspace(*p);
+    if (workspace_bytes < ws.bytes) return RAZOR_ECAPACITY;
+
+    int workers = p->n_workers;
+    if (workers == 0) {
+        int rc = auto_workers(&workers);
+        if (rc != RAZOR_OK) return rc;
+    }
+    workers = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int n_heads = p->batch * p->n_kv_heads, g = p->n_q_heads / p->n_kv_heads;
+    const int D = p->head_dim, has_new = k_new != nullptr;
+    const int rb = D * elem_size(p->dtype);
+    char *wsb = static_cast<char *>(workspace);
+    int32_t *prefix = reinterpret_cast<int32_t *>(wsb + ws.prefix_off);
+    float *ml = reinterpret_cast<float *>(wsb + ws.ml_off);
+    float *acc = reinterpret_cast<float *>(wsb + ws.acc_off);
+    char *a = static_cast<char *>(arena);
+    const char *kn = static_cast<const char *>(k_new), *vn = static_cast<const char *>(v_new);
+    const float sl2e = p->scale * 1.4426950408889634f;
+
+    const dim3 pgrid(n_heads + 1);
+    if (rb == 128)
+        hipLaunchKernelGGL((prepare_kernel<128>), pgrid, dim3(64), 0, s, desc_dev, kn, vn, a, n_heads, workers, prefix);
+    else if (rb == 256)
+        hipLaunchKernelGGL((prepare_kernel<256>), pgrid, dim3(64), 0, s, desc_dev, kn, vn, a, n_heads, workers, prefix);
+    else
+        hipLaunchKernelGGL((prepare_kernel<512>), pgrid, dim3(64), 0, s, desc_dev, kn, vn, a, n_heads, workers, prefix);
+
+    const dim3 grid((workers + 3) / 4);
+    if (g_profile_start) RAZOR_HIP_CHECK(hipEventRecord(g_profile_start, s));
+    if (p->dtype == RAZOR_BF16) {
+        const uint16_t *q = static_cast<const uint16_t *>(Q);
+        if (D == 128)
+            hipLaunchKernelGGL((decode_partial_bf16_kernel<128, 4>), grid, dim3(256), 0, s, q, a, desc_dev,
+                               prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+        else
+            hipLaunchKernelGGL((decode_partial_bf16_kernel<64, 4>), grid, dim3(256), 0, s, q, a, desc_dev,
+                               prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+    } else {
+        const float *q = static_cast<const float *>(Q);
+        if (g == 1) launch_partial_f32<1>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+        else if (g == 2) launch_partial_f32<2>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+        else if (g <= 4) launch_partial_f32<4>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+        else if (g <= 8) launch_partial_f32<8>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+        else launch_partial_f32<16>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+    }
+
+    if (g_profile_stop) RAZOR_HIP_CHECK(hipEventRecord(g_profile_stop, s));
+
+    const dim3 cgrid(p->batch * p->n_q_heads);
+    if (D == 128)
+        hipLaunchKernelGGL((combine_kernel<128>), cgrid, dim3(256), 0, s, Q, p->dtype, comp, desc_dev, prefix,
+                           ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new, p->use_comp, sl2e);
+    else
+        hipLaunchKernelGGL((combine_kernel<64>), cgrid, dim3(256), 0, s, Q, p->dtype, comp, desc_dev, prefix,
+                           ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new, p->use_comp, sl2e);
+    RAZOR_HIP_CHECK(hipGetLastError());
+    return RAZOR_OK;
+}
+
+extern "C" int razor_profile_events(void *ev_start, void *ev_stop)
+{
+    razor::g_profile_start = static_cast<hipEvent_t>(ev_start);
+    razor::g_profile_stop = static_cast<hipEvent_t>(ev_stop);
+    return RAZOR_OK;
+}

@@ -1,0 +1,49 @@
+// Shared host-side definitions of the razor library (not part of the public ABI).
+#ifndef RAZOR_INTERNAL_H
+#define RAZOR_INTERNAL_H
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "razor.h"
+
+namespace razor {
+
+constexpr int kBlockRows = RAZOR_BLOCK_ROWS;  // K rows per arena block
+constexpr int kMeanSlabRows = 1024;           // dropped rows one workgroup sums (Eq.(4))
+constexpr int kMinBlocksPerWorker = 2;        // never split a decode finer than this
+
+inline int elem_size(int dtype) { return dtype == RAZOR_F32 ? 4 : 2; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Where the pieces of the caller's workspace sit.  Decode and compress reuse the
+// same buffer; both layouts start at offset 0.
+struct DecodeWorkspace {
+    size_t prefix_off;  // int32[n_heads + 2]: block prefix sums, then blocks-per-worker
+    size_t ml_off;      // float[slots][g][2]: running max (log2 domain) and denominator
+    size_t acc_off;     // float[slots][g][head_dim]: unnormalised output
+    size_t bytes;
+    int slots;
+};
+DecodeWorkspace decode_workspace(const razor_params &p);
+
+struct CompressWorkspace {
+    size_t partial_off;  // float[n_heads][max_slabs][2][head_dim]
+    size_t bytes;
+    int max_slabs;
+};
+CompressWorkspace compress_workspace(const razor_params &p, int max_dropped);
+
+// Validates p; returns RAZOR_OK or RAZOR_EINVAL.
+int check_params(const razor_params *p);
+
+// Fills desc (size batch * n_kv_heads); returns RAZOR_OK / RAZOR_EINVAL.
+int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *mask,
+               std::vector<razor_head_desc> &desc, razor_sizes &sizes, int &max_dropped);
+
+// Remembers `what` + the HIP error text for razor_strerror; returns RAZOR_EHIP.
+int hip_failure(const char *what, int hip_error);
+
+}  // namespace razor
+#endif

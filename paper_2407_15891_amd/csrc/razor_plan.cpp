@@ -1,0 +1,138 @@
+// Host-only part of the razor library: argument checks, the selection table of
+// Algorithm 1 (steps 2-3), buffer sizes and error text.  No GPU work happens here.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "razor_internal.h"
+
+namespace razor {
+
+static thread_local char g_hip_error_text[256] = "no HIP error recorded";
+
+int hip_failure(const char *what, int hip_error)
+{
+    std::snprintf(g_hip_error_text, sizeof g_hip_error_text, "%s: %s", what,
+                  hipGetErrorString(static_cast<hipError_t>(hip_error)));
+    return RAZOR_EHIP;
+}
+
+int check_params(const razor_params *p)
+{
+    if (!p) return RAZOR_EINVAL;
+    if (p->batch < 1 || p->n_kv_heads < 1 || p->n_q_heads < 1) return RAZOR_EINVAL;
+    if (p->n_q_heads % p->n_kv_heads != 0) return RAZOR_EINVAL;
+    if (p->n_q_heads / p->n_kv_heads > RAZOR_MAX_GROUP) return RAZOR_EINVAL;
+    if (p->head_dim != 64 && p->head_dim != 128) return RAZOR_EINVAL;
+    if (p->n_sink < 0 || p->window < 0 || p->max_new < 0) return RAZOR_EINVAL;
+    if (p->dtype != RAZOR_F32 && p->dtype != RAZOR_BF16) return RAZOR_EINVAL;
+    if (p->out_dtype != RAZOR_F32 && p->out_dtype != RAZOR_BF16) return RAZOR_EINVAL;
+    if (p->use_comp != 0 && p->use_comp != 1) return RAZOR_EINVAL;
+    if (!(p->scale == p->scale) || p->scale <= 0.0f) return RAZOR_EINVAL;
+    if (p->n_workers < 0 || p->n_workers > RAZOR_MAX_WORKERS) return RAZOR_EINVAL;
+    if ((int64_t)p->batch * p->n_kv_heads > (1 << 20)) return RAZOR_EINVAL;
+    return RAZOR_OK;
+}
+
+DecodeWorkspace decode_workspace(const razor_params &p)
+{
+    const size_t n_heads = (size_t)p.batch * p.n_kv_heads;
+    const size_t g = (size_t)(p.n_q_heads / p.n_kv_heads);
+    DecodeWorkspace w;
+    // a (worker, head) segment owns slot worker + head, so slots <= workers + heads
+    w.slots = (int)(RAZOR_MAX_WORKERS + n_heads);
+    w.prefix_off = 0;
+    w.ml_off = round_up((n_heads + 2) * sizeof(int32_t), 256);
+    w.acc_off = w.ml_off + round_up((size_t)w.slots * g * 2 * sizeof(float), 256);
+    w.bytes = w.acc_off + (size_t)w.slots * g * p.head_dim * sizeof(float);
+    return w;
+}
+
+CompressWorkspace compress_workspace(const razor_params &p, int max_dropped)
+{
+    const size_t n_heads = (size_t)p.batch * p.n_kv_heads;
+    CompressWorkspace w;
+    w.max_slabs = (max_dropped + kMeanSlabRows - 1) / kMeanSlabRows;
+    w.partial_off = 0;
+    w.bytes = n_heads * (size_t)w.max_slabs * 2 * p.head_dim * sizeof(float);
+    return w;
+}
+
+int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *mask,
+               std::vector<razor_head_desc> &desc, razor_sizes &sizes, int &max_dropped)
+{
+    const int n_heads = p.batch * p.n_kv_heads;
+    desc.assign((size_t)n_heads, razor_head_desc{});
+    int64_t row_off = 0, kept_off = 0;
+    max_dropped = 0;
+    for (int b = 0; b < p.batch; ++b) {
+        const int64_t N = seq_lens[b];
+        if (N < 1) return RAZOR_EINVAL;
+        for (int h = 0; h < p.n_kv_heads; ++h) {
+            razor_head_desc &e = desc[(size_t)b * p.n_kv_heads + h];
+            const bool retrieval = mask[h] != 0;
+            // Nothing is dropped when sinks and window already cover the sequence: the
+            // mean over an empty set in Eq.(4) is undefined, so the head keeps every row.
+            const bool drops = !retrieval && N > (int64_t)p.n_sink + p.window;
+            const int64_t rows = drops ? (int64_t)p.n_sink + p.window : N;
+            const int64_t cap = (int64_t)round_up((size_t)(rows + p.max_new), kBlockRows);
+            if (cap > INT32_MAX) return RAZOR_EINVAL;
+            e.row_off = row_off;
+            e.kept_off = kept_off;
+            e.rows = (int32_t)rows;
+            e.cap = (int32_t)cap;
+            e.n_dropped = drops ? (int32_t)(N - rows) : 0;
+            e.flags = (retrieval ? RAZOR_HEAD_RETRIEVAL : 0u) | (drops ? RAZOR_HEAD_COMP : 0u);
+            if (e.n_dropped > max_dropped) max_dropped = e.n_dropped;
+            row_off += cap;
+            kept_off += rows;
+        }
+    }
+    const size_t row_bytes = (size_t)2 * p.head_dim * elem_size(p.dtype);
+    sizes.arena_bytes = (uint64_t)row_off * row_bytes;
+    sizes.comp_bytes = (uint64_t)n_heads * 2 * p.head_dim * sizeof(float);
+    sizes.desc_bytes = (uint64_t)n_heads * sizeof(razor_head_desc);
+    sizes.kept_idx_bytes = (uint64_t)kept_off * sizeof(int32_t);
+    const size_t wd = decode_workspace(p).bytes, wc = compress_workspace(p, max_dropped).bytes;
+    sizes.workspace_bytes = round_up(wd > wc ? wd : wc, 256);
+    sizes.total_rows = kept_off;
+    sizes.total_cap = row_off;
+    return RAZOR_OK;
+}
+
+}  // namespace razor
+
+extern "C" int razor_plan(const razor_params *p, const int32_t *seq_lens_host,
+                          const uint8_t *retrieval_mask_host, razor_head_desc *desc_host,
+                          int32_t *kept_idx_host, razor_sizes *sizes)
+{
+    if (razor::check_params(p) != RAZOR_OK) return RAZOR_EINVAL;
+    if (!seq_lens_host || !retrieval_mask_host || !sizes) return RAZOR_EINVAL;
+    std::vector<razor_head_desc> desc;
+    int max_dropped = 0;
+    int rc = razor::build_plan(*p, seq_lens_host, retrieval_mask_host, desc, *sizes, max_dropped);
+    if (rc != RAZOR_OK) return rc;
+    if (desc_host) std::memcpy(desc_host, desc.data(), desc.size() * sizeof(razor_head_desc));
+    if (kept_idx_host) {
+        for (size_t i = 0; i < desc.size(); ++i) {
+            const razor_head_desc &e = desc[i];
+            int32_t *out = kept_idx_host + e.kept_off;
+            // kept position of cache row t: the sinks come first, the window follows the gap
+            const int32_t head = e.n_dropped > 0 ? p->n_sink : e.rows;
+            for (int32_t t = 0; t < e.rows; ++t) out[t] = t < head ? t : t + e.n_dropped;
+        }
+    }
+    return RAZOR_OK;
+}
+
+extern "C" const char *razor_strerror(int status)
+{
+    switch (status) {
+    case RAZOR_OK: return "ok";
+    case RAZOR_EINVAL: return "invalid argument";
+    case RAZOR_ECAPACITY: return "workspace too small";
+    case RAZOR_EHIP: return razor::g_hip_error_text;
+    default: return "unknown status";
+    }
+}

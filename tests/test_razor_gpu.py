@@ -1,0 +1,281 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle on
+the same seeded inputs.
+
+Bars: integer work (row counts, kept positions, copied K/V bits) bit-exact; Eq.(4)
+means within fp32 accumulation error; attention outputs max-abs <= 2e-3 and per-row
+relative L2 error <= 1e-2 (bf16 inputs, fp32 accumulation)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_15891_amd as razor
+from oracle import razor_oracle as orc
+from paper_2407_15891_amd.workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ABS_TOL, REL_TOL = 2e-3, 1e-2
+
+
+# ----------------------------------------------------------------- helpers
+def say(msg):
+    print(msg, flush=True)
+
+
+def check_output(out, ref, what, bf16_out=False):
+    out = out.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(out).all(), what
+    err = np.abs(out - ref)
+    # a bf16 result carries its own half-ulp rounding (2^-9 relative) on top of the arithmetic
+    tol = ABS_TOL + (np.abs(ref) * 2.0 ** -8 if bf16_out else 0.0)
+    assert (err <= tol).all(), f"{what}: max-abs {err.max():.3e}"
+    rel = np.linalg.norm(out - ref, axis=-1) / np.maximum(np.linalg.norm(ref, axis=-1), 1e-30)
+    assert rel.max() <= REL_TOL, f"{what}: row-relative {rel.max():.3e}"
+    return err.max(), rel.max()
+
+
+def arena_rows(cache, desc, i):
+    """(K rows, V rows) of head i as raw bytes [rows, row_bytes], K de-tiled."""
+    p = cache.params
+    rb = p.head_dim * (4 if p.dtype == razor.RAZOR_F32 else 2)
+    e = desc[i]
+    base = int(e["row_off"]) * 2 * rb
+    cap, rows = int(e["cap"]), int(e["rows"])
+    arena = cache.arena.cpu().numpy()
+    kplane = arena[base: base + cap * rb].reshape(cap // 16, rb // 16, 16, 16)   # [block, piece, row, 16 B]
+    k = kplane.transpose(0, 2, 1, 3).reshape(cap, rb)
+    v = arena[base + cap * rb: base + 2 * cap * rb].reshape(cap, rb)
+    return k[:rows], v[:rows]
+
+
+def raw_bytes(t):
+    """[..., d] tensor -> numpy uint8 [..., d * itemsize]."""
+    a = orc.as_raw(t.cpu())
+    return np.ascontiguousarray(a).view(np.uint8).reshape(*a.shape[:-1], -1)
+
+
+def make_pair(w, **kw):
+    cache = razor.RazorCache.from_workload(w, want_kept_idx=True, **kw)
+    cache.compress(w.K, w.V)
+    oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, w.n_sink, w.window, max_new=max(w.max_new, 1))
+    return cache, oc
+
+
+def check_compress(w, cache, oc, what):
+    desc = cache.desc()
+    kept_dev = cache.kept_idx_dev.cpu().numpy()
+    comp = cache.comp.cpu().numpy().reshape(w.B, w.Hkv, 2, w.d).astype(np.float64)
+    Kb, Vb = raw_bytes(w.K), raw_bytes(w.V)
+    np.testing.assert_array_equal(desc, cache.desc_host)                      # device table == planned table
+    scale_in = float(w.K.abs().max())
+    for b in range(w.B):
+        for h in range(w.Hkv):
+            i = b * w.Hkv + h
+            e = desc[i]
+            kept = oc.kept_of(b, h)
+            assert e["rows"] == len(kept) and e["n_dropped"] == oc.N_d[b, h], what
+            np.testing.assert_array_equal(kept_dev[e["kept_off"]: e["kept_off"] + e["rows"]], kept)
+            k, v = arena_rows(cache, desc, i)
+            np.testing.assert_array_equal(k, Kb[b, h][kept], err_msg=f"{what} K rows head {i}")
+            np.testing.assert_array_equal(v, Vb[b, h][kept], err_msg=f"{what} V rows head {i}")
+            np.testing.assert_allclose(comp[b, h, 0], oc.khat[b, h], rtol=0, atol=4e-6 * scale_in, err_msg=what)
+            np.testing.assert_allclose(comp[b, h, 1], oc.vhat[b, h], rtol=0, atol=4e-6 * scale_in, err_msg=what)
+
+
+def run_steps(w, cache, oc, steps, what, append=True, use_comp=True, bf16_out=False):
+    worst = (0.0, 0.0)
+    for t in range(steps):
+        Q, k, v = w.step_inputs(t, append=append)
+        out = cache.decode(Q, k, v)
+        if append:
+            oc.append(k.cpu(), v.cpu())
+        ref = oc.decode(Q.cpu(), w.scale, use_comp=use_comp)
+        e = check_output(out, ref, f"{what} step {t}", bf16_out)
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+    say(f"    {what}: {steps} step(s), max-abs {worst[0]:.2e}, row-rel {worst[1]:.2e}")
+
+
+# ----------------------------------------------------------------- compress
+@pytest.mark.parametrize("cfg,context,window,batch", [
+    (1, 2048, 256, 1),        # config 1 at full size
+    (1, 1000, 100, 3),        # ragged tail: 104 kept rows = 6.5 blocks
+    (2, 3000, None, 1),
+    (3, 5000, 700, 2),
+    (4, 6000, 333, 5),        # ragged sequence lengths
+])
+def test_compress_parity(cfg, context, window, batch):
+    say(f"compress parity cfg={cfg} context={context} window={window} batch={batch}")
+    w = make_workload(cfg, DEV, context=context, window=window, batch=batch, max_new=3)
+    cache, oc = make_pair(w)
+    check_compress(w, cache, oc, f"cfg{cfg}")
+
+
+def test_compress_strided_input_and_fp32_dim128():
+    say("compress parity: strided K/V views, fp32 head_dim 128, bf16 head_dim 64")
+    for dtype, d in ((torch.float32, 128), (torch.bfloat16, 64), (torch.float32, 64), (torch.bfloat16, 128)):
+        g = torch.Generator(device=DEV); g.manual_seed(77)
+        big_k = torch.randn(2, 3, 777, d + 16, generator=g, device=DEV).to(dtype)
+        big_v = torch.randn(2, 3, 777, d + 16, generator=g, device=DEV).to(dtype)
+        K, V = big_k[:, :, 5:705, 8:8 + d], big_v[:, :, 5:705, 8:8 + d]      # 16-byte aligned views
+        seq, mask = np.array([700, 431], np.int32), np.array([0, 1, 0], np.uint8)
+        cache = razor.RazorCache(batch=2, n_q_heads=6, n_kv_heads=3, head_dim=d, seq_lens=seq,
+                                 retrieval_mask=mask, n_sink=4, window=50, max_new=2, dtype=dtype,
+                                 device=DEV, want_kept_idx=True)
+        cache.compress(K, V)
+        oc = orc.OracleCache(K.cpu().contiguous(), V.cpu().contiguous(), seq, mask, 4, 50, max_new=2)
+
+        class W:  # the few fields check_compress reads
+            pass
+        w = W(); w.B, w.Hkv, w.d, w.K, w.V = 2, 3, d, K.contiguous(), V.contiguous()
+        check_compress(w, cache, oc, f"strided {dtype} d={d}")
+        # and the cache answers queries correctly
+        Q = torch.randn(2, 6, d, generator=g, device=DEV).to(dtype)
+        check_output(cache.decode(Q), oc.decode(Q.cpu(), d ** -0.5), f"strided {dtype} d={d}")
+
+
+# ----------------------------------------------------------------- decode
+@pytest.mark.parametrize("cfg,context,window,batch,workers", [
+    (1, 2048, 256, 1, 0),      # config 1, fp32 MHA
+    (1, 777, 90, 2, 16),       # few workers: every wave crosses head boundaries
+    (2, 4096, None, 1, 0),     # bf16 MHA with outlier channels
+    (2, 1500, 200, 2, 64),
+    (3, 9000, 1000, 2, 0),     # GQA g = 4
+    (3, 3001, 500, 3, 24),
+    (4, 8000, 300, 4, 0),      # GQA g = 8, ragged lengths
+    (4, 2500, 77, 6, 40),
+])
+def test_decode_parity(cfg, context, window, batch, workers):
+    say(f"decode parity cfg={cfg} context={context} window={window} batch={batch} workers={workers}")
+    w = make_workload(cfg, DEV, context=context, window=window, batch=batch, max_new=20)
+    cache, oc = make_pair(w, n_workers=workers)
+    run_steps(w, cache, oc, 1, "no append", append=False)
+    run_steps(w, cache, oc, 20, "with append")           # crosses a 16-row block boundary
+    d = cache.desc()
+    np.testing.assert_array_equal(d["rows"], oc.rows().reshape(-1))
+    assert not (d["flags"] & razor.RAZOR_HEAD_OVERFLOW).any()
+
+
+@pytest.mark.parametrize("cfg", [1, 3])
+def test_decode_special_cases(cfg):
+    say(f"decode special cases cfg={cfg}")
+    base = dict(context=1200, batch=2, max_new=2)
+    # every head retrieval; nothing dropped (window covers); single dropped token; comp token only
+    Hkv = 8
+    for name, kw in (("all retrieval", dict(window=100, mask=np.ones(Hkv, np.uint8))),
+                     ("window covers context", dict(window=1196)),
+                     ("one dropped token", dict(window=1195)),
+                     ("no window", dict(window=0)),
+                     ("short window", dict(window=5))):
+        w = make_workload(cfg, DEV, **base, **kw)
+        cache, oc = make_pair(w)
+        run_steps(w, cache, oc, 2, name)
+    # ablation: compensation term off
+    w = make_workload(cfg, DEV, window=64, **base)
+    cache, oc = make_pair(w, use_comp=False)
+    run_steps(w, cache, oc, 2, "use_comp=0", use_comp=False)
+    # bf16 output
+    if w.dtype == torch.bfloat16:
+        cache, oc = make_pair(w, out_dtype=torch.bfloat16)
+        run_steps(w, cache, oc, 2, "bf16 output", bf16_out=True)
+
+
+def test_decode_only_compensation_token():
+    say("decode: heads that keep no row at all (n_sink = 0, window = 0)")
+    w = make_workload(3, DEV, context=500, window=0, batch=2, max_new=2)
+    w.n_sink = 0
+    cache, oc = make_pair(w)
+    run_steps(w, cache, oc, 1, "comp token only", append=False)
+    run_steps(w, cache, oc, 2, "comp token + appended rows")
+
+
+def test_decode_peaked_queries_exercise_absolute_bound():
+    say("decode: queries aligned with one cached key (outputs of order 1)")
+    for cfg in (1, 2, 3):
+        w = make_workload(cfg, DEV, context=3000, window=400, batch=2, max_new=1)
+        cache, oc = make_pair(w)
+        g = w.Hq // w.Hkv
+        rng = np.random.default_rng(5)
+        Q = torch.empty(w.B, w.Hq, w.d, device=DEV, dtype=w.dtype)
+        for b in range(w.B):
+            for j in range(w.Hq):
+                kept = oc.kept_of(b, j // g)
+                Q[b, j] = w.K[b, j // g, int(rng.choice(kept))] * 4
+        out = cache.decode(Q)
+        ref = oc.decode(Q.cpu(), w.scale)
+        assert np.abs(ref).max() > 0.5
+        e = check_output(out, ref, f"peaked cfg{cfg}")
+        say(f"    peaked cfg{cfg}: max-abs {e[0]:.2e}, row-rel {e[1]:.2e}, max|ref| {np.abs(ref).max():.2f}")
+
+
+def test_decode_is_bit_reproducible():
+    say("decode: same inputs twice -> identical bits")
+    w = make_workload(3, DEV, context=20000, window=3000, batch=2, max_new=1)
+    cache, _ = make_pair(w)
+    Q, _, _ = w.step_inputs(0, append=False)
+    a = cache.decode(Q).clone()
+    comp_a = cache.comp.clone()
+    cache.compress(w.K, w.V)
+    b = cache.decode(Q)
+    assert torch.equal(a, b) and torch.equal(comp_a, cache.comp)
+
+
+def test_append_overflow_sets_flag_and_keeps_answering():
+    say("decode: append beyond cap sets the overflow flag, no fault")
+    w = make_workload(1, DEV, context=300, window=12, batch=1, max_new=0)   # rows 16 -> cap 16, full
+    cache, oc = make_pair(w)
+    assert (cache.desc_host["cap"][cache.desc_host["n_dropped"] > 0] == 16).all()
+    Q, k, v = w.step_inputs(0)
+    out = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=DEV)
+    rc = razor.razor_decode_attn(cache.params, Q, k, v, cache.arena, cache.comp, cache.desc_dev, out,
+                                 cache.workspace, cache.workspace.numel(), 0)
+    assert rc == razor.RAZOR_OK
+    torch.cuda.synchronize()
+    d = cache.desc()
+    full = d["rows"] == d["cap"]
+    assert full.any() and ((d["flags"] & razor.RAZOR_HEAD_OVERFLOW) != 0)[full].all()
+    # full heads answered without the new token; the others (retrieval heads: 300 rows, cap 304) took it
+    ref_without = oc.decode(Q.cpu(), w.scale)
+    oc.append(k.cpu(), v.cpu())
+    ref_with = oc.decode(Q.cpu(), w.scale)
+    ref = np.where(np.repeat(full.reshape(w.B, w.Hkv), w.Hq // w.Hkv, 1)[..., None], ref_without, ref_with)
+    check_output(out, ref, "overflow")
+
+
+# ----------------------------------------------------------------- full-size configurations
+def test_full_size_config2():
+    say("full size: config 2 (32 heads x 32768 x 128 bf16), compress + 64 decode steps")
+    w = make_workload(2, DEV)
+    cache, oc = make_pair(w)
+    check_compress(w, cache, oc, "config 2")
+    run_steps(w, cache, oc, w.decode_steps, "config 2")
+
+
+def test_full_size_config3():
+    say("full size: config 3 (4 x 8 KV heads x 131072 x 128 bf16, g = 4)")
+    w = make_workload(3, DEV)
+    cache, oc = make_pair(w)
+    say("    compressed; checking tables and means")
+    desc = cache.desc()
+    np.testing.assert_array_equal(desc["rows"], oc.rows().reshape(-1))
+    np.testing.assert_array_equal(desc["n_dropped"], oc.N_d.reshape(-1))
+    comp = cache.comp.cpu().numpy().reshape(w.B, w.Hkv, 2, w.d).astype(np.float64)
+    np.testing.assert_allclose(comp[:, :, 0], oc.khat, rtol=0, atol=3e-5)
+    np.testing.assert_allclose(comp[:, :, 1], oc.vhat, rtol=0, atol=3e-5)
+    # sampled heads: copied bits
+    Kb, Vb = raw_bytes(w.K[:1]), raw_bytes(w.V[:1])
+    for h in range(w.Hkv):
+        k, v = arena_rows(cache, desc, h)
+        np.testing.assert_array_equal(k, Kb[0, h][oc.kept_of(0, h)])
+        np.testing.assert_array_equal(v, Vb[0, h][oc.kept_of(0, h)])
+    run_steps(w, cache, oc, 1, "config 3", append=False)
+    run_steps(w, cache, oc, 1, "config 3 append")
+
+
+def test_full_size_config4():
+    say("full size: config 4 (16 ragged sequences, 8 KV heads, g = 8)")
+    w = make_workload(4, DEV)
+    cache, oc = make_pair(w)
+    desc = cache.desc()
+    np.testing.assert_array_equal(desc["rows"], oc.rows().reshape(-1))
+    np.testing.assert_array_equal(desc["n_dropped"], oc.N_d.reshape(-1))
+    run_steps(w, cache, oc, 1, "config 4")

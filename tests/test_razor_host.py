@@ -1,0 +1,143 @@
+"""CPU-only checks of the HIP library's host side: it loads, exports what the header
+declares, plans exactly the table the oracle derives from Algorithm 1, and turns bad
+arguments into error codes before touching a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2407_15891_amd as razor
+from oracle import razor_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def params(**kw):
+    base = dict(batch=2, n_q_heads=8, n_kv_heads=4, head_dim=128, n_sink=4, window=32, max_new=8,
+                use_comp=1, dtype=razor.RAZOR_BF16, out_dtype=razor.RAZOR_F32, scale=0.088, n_workers=0)
+    base.update(kw)
+    return razor.RazorParams(**base)
+
+
+def plan(p, seq_lens, mask, want_idx=True):
+    seq_lens = np.asarray(seq_lens, np.int32)
+    mask = np.asarray(mask, np.uint8)
+    sizes = razor.RazorSizes()
+    rc = razor.razor_plan(p, seq_lens, mask, None, None, sizes)
+    if rc != razor.RAZOR_OK:
+        return rc, None, None, None
+    desc = np.zeros(p.batch * p.n_kv_heads, razor.DESC_DTYPE)
+    idx = np.zeros(max(sizes.total_rows, 1), np.int32) if want_idx else None
+    rc = razor.razor_plan(p, seq_lens, mask, desc, idx, sizes)
+    return rc, desc, idx, sizes
+
+
+def test_library_exports_every_declared_symbol():
+    lib = razor.load_library()
+    header = open(os.path.join(ROOT, "include", "razor.h")).read()
+    declared = set(re.findall(r"\b(razor_[a-z_]+)\s*\(", header))
+    assert declared == set(razor.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert razor.razor_strerror(razor.RAZOR_OK) == "ok"
+    assert "invalid" in razor.razor_strerror(razor.RAZOR_EINVAL)
+    assert "workspace" in razor.razor_strerror(razor.RAZOR_ECAPACITY)
+    assert ctypes.sizeof(razor.RazorHeadDesc) == 32 and ctypes.sizeof(razor.RazorParams) == 48
+
+
+@pytest.mark.parametrize("seq_lens,mask,n_sink,window", [
+    ([2048], [1, 0, 0, 0, 0, 1, 0, 0], 4, 256),           # config 1
+    ([100, 37, 5, 36], [0, 1, 0, 0], 4, 32),               # ragged; 36 = exactly covered; 37 drops one
+    ([64, 64], [0, 0, 0, 0], 0, 16),                       # no sinks
+    ([64, 64], [0, 0, 1, 0], 4, 0),                        # no window
+    ([50, 1], [0, 0, 0, 0], 0, 0),                         # nothing kept but the compensation token
+    ([131072, 131072], [0, 1, 0, 0], 4, 19660),            # config 3 lengths
+])
+def test_plan_matches_oracle_table(seq_lens, mask, n_sink, window):
+    B, H = len(seq_lens), len(mask)
+    p = params(batch=B, n_kv_heads=H, n_q_heads=H, n_sink=n_sink, window=window)
+    rc, desc, idx, sizes = plan(p, seq_lens, mask)
+    assert rc == razor.RAZOR_OK
+    total = 0
+    for b in range(B):
+        for h in range(H):
+            e = desc[b * H + h]
+            kept, lo, hi = orc.select(seq_lens[b], bool(mask[h]), n_sink, window)
+            assert e["rows"] == len(kept) and e["n_dropped"] == hi - lo          # bit-exact lengths
+            assert e["kept_off"] == total
+            np.testing.assert_array_equal(idx[total: total + len(kept)], kept)   # bit-exact positions
+            assert bool(e["flags"] & razor.RAZOR_HEAD_RETRIEVAL) == bool(mask[h])
+            assert bool(e["flags"] & razor.RAZOR_HEAD_COMP) == (hi > lo)
+            total += len(kept)
+    assert sizes.total_rows == total
+    # layout: regions are disjoint, in order, block-aligned, with room for the appends
+    off = 0
+    for e in desc:
+        assert e["row_off"] == off and e["cap"] % razor.RAZOR_BLOCK_ROWS == 0
+        assert e["rows"] + p.max_new <= e["cap"] < e["rows"] + p.max_new + razor.RAZOR_BLOCK_ROWS
+        off += e["cap"]
+    assert sizes.total_cap == off
+    assert sizes.arena_bytes == off * 2 * p.head_dim * 2
+    assert sizes.comp_bytes == B * H * 2 * p.head_dim * 4 and sizes.desc_bytes == B * H * 32
+    assert sizes.kept_idx_bytes == 4 * total and sizes.workspace_bytes > 0
+
+
+def test_plan_reproduces_table2_ratio():
+    # 15 % retrieval heads, buffer max(4000, N/5), 4 sinks -> 3.125x (Table 2 caption)
+    N, H = 1_000_000, 20
+    mask = np.zeros(H, np.uint8); mask[:3] = 1
+    p = params(batch=1, n_kv_heads=H, n_q_heads=H, n_sink=4, window=max(4000, N // 5), max_new=0)
+    rc, desc, _, sizes = plan(p, [N], mask, want_idx=False)
+    assert rc == razor.RAZOR_OK
+    assert H * N / sizes.total_rows == pytest.approx(3.125, rel=1e-4)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(head_dim=96), dict(head_dim=256), dict(n_q_heads=6), dict(n_q_heads=4 * 32), dict(batch=0),
+    dict(n_sink=-1), dict(window=-1), dict(max_new=-1), dict(dtype=2), dict(out_dtype=7),
+    dict(use_comp=2), dict(scale=0.0), dict(scale=float("nan")), dict(n_workers=-1),
+    dict(n_workers=razor.RAZOR_MAX_WORKERS + 1),
+])
+def test_bad_params_are_rejected(kw):
+    p = params(**kw)
+    sizes = razor.RazorSizes()
+    seq = np.full(max(p.batch, 1), 100, np.int32)
+    mask = np.zeros(p.n_kv_heads, np.uint8)
+    assert razor.razor_plan(p, seq, mask, None, None, sizes) == razor.RAZOR_EINVAL
+
+
+def test_bad_arguments_are_rejected_before_any_gpu_work():
+    p = params()
+    seq = np.array([100, 0], np.int32)            # empty sequence
+    mask = np.zeros(4, np.uint8)
+    sizes = razor.RazorSizes()
+    assert razor.razor_plan(p, seq, mask, None, None, sizes) == razor.RAZOR_EINVAL
+    assert razor.razor_plan(p, seq, mask, None, None, None) == razor.RAZOR_EINVAL
+    L = razor.load_library()
+    pp = ctypes.byref(p)
+    seq = np.array([100, 100], np.int32)
+    fake = 4096   # never dereferenced: validation fails first
+    # null tensors
+    assert L.razor_compress(pp, None, fake, 1, 1, 128, seq.ctypes.data, mask.ctypes.data, fake, fake,
+                            fake, None, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+    # row stride shorter than a row / misaligned stride / misaligned pointer
+    for strides, k in (((100 * 64, 64, 64), fake), ((100 * 132, 132 * 100, 132), fake),
+                       ((100 * 128 * 4, 100 * 128, 128), fake + 2)):
+        assert L.razor_compress(pp, k, fake, *strides, seq.ctypes.data, mask.ctypes.data, fake, fake,
+                                fake, None, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+    # workspace too small
+    assert L.razor_compress(pp, fake, fake, 4 * 100 * 128, 100 * 128, 128, seq.ctypes.data,
+                            mask.ctypes.data, fake, fake, fake, None, fake, 16, None) == razor.RAZOR_ECAPACITY
+    assert L.razor_decode_attn(pp, fake, None, None, fake, fake, fake, fake, fake, 16, None) == razor.RAZOR_ECAPACITY
+    assert L.razor_decode_attn(pp, None, None, None, fake, fake, fake, fake, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+    # k_new without v_new
+    assert L.razor_decode_attn(pp, fake, fake, None, fake, fake, fake, fake, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(razor, "_lib", None)
+    monkeypatch.setattr(razor, "LIB_PATH", "/nonexistent/librazor.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        razor.load_library()
