@@ -111,15 +111,15 @@ __device__ __forceinline__ int find_head(const int32_t *__restrict__ prefix, int
 // Lane l = 16 * kg + n.  For one 16-row block:
 //   S[row][head]  = K[row][:] . Q[head][:]    v_mfma_f32_16x16x32_bf16, A = K block, B = Q
 //                   lane (kg, n) ends up with head n, rows 4*kg .. 4*kg+3
-//   P             = exp2(S - max), rounded to bf16, still in those lanes: it is already
-//                   the B operand of the second product
-//   O^T[col][head] += V^T[col][row] . P[row][head]   v_mfma_f32_16x16x16_bf16, A = V^T
+//   P             = exp2(S - max), split into a bf16 pair hi + lo, still in those lanes: it
+//                   is already the B operand of the second product
+//   O^T[col][head] += V^T[col][row] . P[row][head]   v_mfma_f32_16x16x32_bf16, A = V^T twice
 //                   lane (kg, n) loads 16 bytes of rows 4*kg .. 4*kg+3 (coalesced), and a
 //                   4-row in-lane transpose (v_perm_b32) yields A for one column phase e
 //                   lane (kg, n) accumulates head n, columns 4*VE*kg .. 4*VE*kg + 4*VE-1
 // The K plane is stored piece-major per block, so the A operand of the first product is
-// one contiguous 1 KB load per 32 columns.  The denominator sums the bf16-rounded P, the
-// same numbers the matrix core multiplies, so numerator and denominator stay consistent.
+// one contiguous 1 KB load per 32 columns.  A single bf16 P (2^-9 per weight) would miss
+// the 2e-3 absolute bound on caches with large-magnitude value channels; hi + lo does not.
 template <int D, int PF>
 __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
     const uint16_t *__restrict__ Q, const char *__restrict__ arena,
@@ -197,13 +197,18 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
             const float m_new = fmaxf(m, bmax);     // finite: every block holds a valid row
             const float alpha = fast_exp2(m - m_new);
             m = m_new;
-            s16x4 pk;
+            // P goes to the matrix core as a bf16 pair hi + lo (p = hi + lo to 2^-17), stacked along
+            // the contraction axis against two copies of the V rows, so one 16x16x32 product
+            // accumulates V^T.(P_hi + P_lo); the denominator sums the fp32 p.
+            bf16x8 pk;
             float psum = 0.f;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const __bf16 pb = (__bf16)fast_exp2(sv[r] - m_new);
-                psum += (float)pb;
-                pk[r] = __builtin_bit_cast(short, pb);
+                const float pr = fast_exp2(sv[r] - m_new);
+                const __bf16 hi = (__bf16)pr;
+                pk[r] = hi;
+                pk[4 + r] = (__bf16)(pr - (float)hi);
+                psum += pr;
             }
             l = l * alpha + psum;
 #pragma unroll
@@ -213,11 +218,13 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
                 const uint32_t w1 = reinterpret_cast<const uint32_t *>(&v[1])[c >> 1];
                 const uint32_t w2 = reinterpret_cast<const uint32_t *>(&v[2])[c >> 1];
                 const uint32_t w3 = reinterpret_cast<const uint32_t *>(&v[3])[c >> 1];
-                uint2 packed;
+                uint4 packed;
                 packed.x = __builtin_amdgcn_perm(w1, w0, sel);   // rows 4kg, 4kg+1 of column phase c
                 packed.y = __builtin_amdgcn_perm(w3, w2, sel);   // rows 4kg+2, 4kg+3
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                    __builtin_bit_cast(s16x4, packed), pk, acc[c] * alpha, 0, 0, 0);
+                packed.z = packed.x;
+                packed.w = packed.y;
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    __builtin_bit_cast(bf16x8, packed), pk, acc[c] * alpha, 0, 0, 0);
             }
         };
 
