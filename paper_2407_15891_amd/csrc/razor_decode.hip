@@ -1,19 +1,20 @@
 // razor_decode_attn: one decode step over the per-head heterogeneous cache
-// (Algorithm 1 step 5, Eq.(5)).  Three launches on the caller's stream:
+// (Algorithm 1 step 5, Eq.(5)).  Two launches on the caller's stream:
 //
-//   prepare   appends the new token to every head and writes, per head, the prefix
-//             sum of its 16-row block count -- the ragged length table flattened
-//             into one block axis.
-//   partial   the flattened block axis is cut into equal ranges, one per wavefront.
-//             A wavefront streams the K and V blocks of its range once from HBM with
-//             128-bit loads held in registers several blocks ahead, keeps an online
+//   partial   the ragged per-head length table is flattened into one axis of 16-row
+//             blocks, and that axis is cut into equal ranges, one per wavefront (every
+//             wave derives the cut itself from the descriptor table).  A wavefront
+//             streams the K and V blocks of its range once from HBM with 128-bit
+//             non-temporal loads held in registers several blocks ahead, keeps an online
 //             softmax state (running max, denominator, unnormalised output) for the
-//             whole query group of the KV head, and stores one partial state per
-//             head segment it touched.  Long retrieval heads and short compressed
-//             heads therefore cost exactly their bytes; no wavefront idles behind
-//             another, and waves never synchronise with each other.
+//             whole query group of the KV head, and stores one partial state per head
+//             segment it touched.  Long retrieval heads and short compressed heads cost
+//             exactly their bytes; no wavefront idles behind another, and waves never
+//             synchronise with each other.  The wave that owns the block a new token
+//             falls into stores that token first (the append).
 //   combine   merges the partial states of each query head in a fixed order, folds
-//             in the compensation token with weight N_d (logit + ln N_d), normalises.
+//             in the compensation token with weight N_d (logit + ln N_d), normalises,
+//             and makes the append permanent (rows += 1).
 //
 // bf16 caches use the matrix cores for both products (the query group is padded to
 // the 16-wide operand); fp32 caches use vector FMAs.
@@ -52,67 +53,109 @@ __device__ __forceinline__ int rows_this_step(const razor_head_desc &e, int has_
     return e.rows + ((has_new && e.rows < e.cap) ? 1 : 0);
 }
 
-// ---------------------------------------------------------------- prepare
-template <int RB>
-__global__ __launch_bounds__(64) void prepare_kernel(
-    const razor_head_desc *__restrict__ desc, const char *__restrict__ k_new,
-    const char *__restrict__ v_new, char *__restrict__ arena, int n_heads, int n_workers,
-    int32_t *__restrict__ prefix)
+// ---------------------------------------------------------------- the flattened block axis
+__device__ __forceinline__ int wave_sum(int v)
 {
-    constexpr int LPR = RB / 16;
-    const int lane = threadIdx.x;
-    if ((int)blockIdx.x < n_heads) {           // append one row to head blockIdx.x
-        if (!k_new) return;
-        const razor_head_desc e = desc[blockIdx.x];
-        if (e.rows >= e.cap) return;
-        const int t = e.rows;
-        char *kplane = arena + e.row_off * 2 * RB;
-        char *vplane = kplane + (int64_t)e.cap * RB;
-        if (lane < LPR) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(k_new + (int64_t)blockIdx.x * RB + lane * 16);
-            char *blk = kplane + (int64_t)(t / kBlockRows) * kBlockRows * RB;
-            *reinterpret_cast<uint4 *>(blk + (lane * 16 + t % kBlockRows) * 16) = v;
-        } else if (lane >= 32 && lane < 32 + LPR) {
-            const int piece = lane - 32;
-            const uint4 v = *reinterpret_cast<const uint4 *>(v_new + (int64_t)blockIdx.x * RB + piece * 16);
-            *reinterpret_cast<uint4 *>(vplane + (int64_t)t * RB + piece * 16) = v;
-        }
-        return;
-    }
-    // last workgroup: prefix sums of the block counts
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// 16-row blocks head idx holds this step (0 for idx >= n_heads).
+__device__ __forceinline__ int head_blocks(const razor_head_desc *__restrict__ desc, int idx,
+                                           int n_heads, int has_new)
+{
+    if (idx >= n_heads) return 0;
+    const int2 rc = *reinterpret_cast<const int2 *>(reinterpret_cast<const char *>(desc + idx) + 16);
+    const int rows = rc.x + ((has_new && rc.x < rc.y) ? 1 : 0);   // {rows, cap}
+    return (rows + kBlockRows - 1) / kBlockRows;
+}
+
+// Blocks per worker for this step: the flattened axis cut into n_workers equal ranges.
+__device__ __forceinline__ int blocks_per_worker(int total, int n_workers)
+{
+    const int per = (total + n_workers - 1) / n_workers;
+    return per < kMinBlocksPerWorker ? kMinBlocksPerWorker : per;
+}
+
+// Wave-cooperative.  Sum of head_blocks over all heads.
+__device__ __forceinline__ int total_blocks(const razor_head_desc *__restrict__ desc, int n_heads,
+                                            int has_new, int lane)
+{
+    int acc = 0;
+    for (int base = 0; base < n_heads; base += 64) acc += head_blocks(desc, base + lane, n_heads, has_new);
+    return wave_sum(acc);
+}
+
+// Wave-cooperative.  The head that owns flattened block `blk` (< total) and the flattened
+// index of that head's first block.
+__device__ __forceinline__ void locate_block(const razor_head_desc *__restrict__ desc, int n_heads,
+                                             int has_new, int lane, int blk, int &head, int &first)
+{
     int carry = 0;
+    head = 0;
+    first = 0;
     for (int base = 0; base < n_heads; base += 64) {
-        const int idx = base + lane;
-        int incl = 0;
-        if (idx < n_heads)
-            incl = (rows_this_step(desc[idx], k_new != nullptr) + kBlockRows - 1) / kBlockRows;
+        int incl = head_blocks(desc, base + lane, n_heads, has_new);
+#pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const int up = __shfl_up(incl, o);
             if (lane >= o) incl += up;
         }
-        if (idx < n_heads) prefix[idx + 1] = carry + incl;
+        const int end = carry + incl;                      // flattened end of head base + lane
+        const int c = __popcll(__ballot(end <= blk));      // ends are non-decreasing
+        if (c < 64) {
+            head = base + c;
+            first = c == 0 ? carry : __shfl(end, c - 1);
+            return;
+        }
+        carry = __shfl(end, 63);
+    }
+}
+
+// Wave-cooperative.  prefix[i] = flattened index of head i's first block, prefix[n_heads] =
+// total, prefix[n_heads + 1] = blocks per worker: what the combine kernel needs to find the
+// partial states of a head.
+__device__ __forceinline__ void write_prefix(const razor_head_desc *__restrict__ desc, int n_heads,
+                                             int has_new, int lane, int per,
+                                             int32_t *__restrict__ prefix)
+{
+    int carry = 0;
+    for (int base = 0; base < n_heads; base += 64) {
+        int incl = head_blocks(desc, base + lane, n_heads, has_new);
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
+        }
+        if (base + lane < n_heads) prefix[base + lane + 1] = carry + incl;
         carry += __shfl(incl, 63);
     }
     if (lane == 0) {
         prefix[0] = 0;
-        int per = (carry + n_workers - 1) / n_workers;
-        prefix[n_heads + 1] = per < kMinBlocksPerWorker ? kMinBlocksPerWorker : per;
+        prefix[n_heads + 1] = per;
     }
 }
 
-// Index of the head that owns flattened block `blk` (wave-uniform).
-__device__ __forceinline__ int find_head(const int32_t *__restrict__ prefix, int n_heads, int blk,
-                                         int lane)
+// The new token of head `head` goes to row e.rows of its planes (K piece-major inside its
+// block, V row-major).  Called by the one wave whose range holds that row's block.
+template <int RB>
+__device__ __forceinline__ void append_row(const razor_head_desc &e, int head, char *kplane, char *vplane,
+                                           const char *__restrict__ k_new,
+                                           const char *__restrict__ v_new, int lane)
 {
-    int count = 0;
-    for (int base = 0; base < n_heads; base += 64) {
-        const int idx = base + lane;
-        const bool ended = idx < n_heads && prefix[idx + 1] <= blk;
-        const int c = __popcll(__ballot(ended));
-        count += c;
-        if (c < 64) break;
+    constexpr int LPR = RB / 16;
+    const int t = e.rows;
+    if (lane < LPR) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(k_new + (int64_t)head * RB + lane * 16);
+        char *blk = kplane + (int64_t)(t / kBlockRows) * kBlockRows * RB;
+        *reinterpret_cast<uint4 *>(blk + (lane * 16 + t % kBlockRows) * 16) = v;
+    } else if (lane >= 32 && lane < 32 + LPR) {
+        const int piece = lane - 32;
+        const uint4 v = *reinterpret_cast<const uint4 *>(v_new + (int64_t)head * RB + piece * 16);
+        *reinterpret_cast<uint4 *>(vplane + (int64_t)t * RB + piece * 16) = v;
     }
-    return count;
+    __threadfence();   // the loads of this wave that follow must see the row
 }
 
 // ---------------------------------------------------------------- partial, bf16 / matrix cores
@@ -131,10 +174,11 @@ __device__ __forceinline__ int find_head(const int32_t *__restrict__ prefix, int
 // the 2e-3 absolute bound on caches with large-magnitude value channels; hi + lo does not.
 template <int D, int PF>
 __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
-    const uint16_t *__restrict__ Q, const char *__restrict__ arena,
-    const razor_head_desc *__restrict__ desc, const int32_t *__restrict__ prefix,
-    float *__restrict__ part_ml, float *__restrict__ part_acc, int n_heads, int n_kv_heads, int g,
-    int has_new, float scale_log2e)
+    const uint16_t *__restrict__ Q, char *__restrict__ arena,
+    const razor_head_desc *__restrict__ desc, const char *__restrict__ k_new,
+    const char *__restrict__ v_new, int32_t *__restrict__ prefix, float *__restrict__ part_ml,
+    float *__restrict__ part_acc, int n_heads, int n_kv_heads, int g, int n_workers,
+    float scale_log2e)
 {
     constexpr int RB = D * 2;     // bytes per row
     constexpr int NS = D / 32;    // K loads (= first-product steps) per block
@@ -144,21 +188,31 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
     const int lane = threadIdx.x & 63;
     const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int kg = lane >> 4, n = lane & 15;
-    const int per = prefix[n_heads + 1], total = prefix[n_heads];
+    const int has_new = k_new != nullptr;
+    const int total = total_blocks(desc, n_heads, has_new, lane);
+    const int per = blocks_per_worker(total, n_workers);
+    if (w == 0) write_prefix(desc, n_heads, has_new, lane, per, prefix);
     int lo = w * per;
     const int hi = lo + per < total ? lo + per : total;
     if (lo >= hi) return;
-    int i = find_head(prefix, n_heads, lo, lane);
+    int i, first;
+    locate_block(desc, n_heads, has_new, lane, lo, i, first);
 
     while (lo < hi) {
-        while (prefix[i + 1] <= lo) ++i;
-        const int first = prefix[i];
-        const int seg_end = hi < prefix[i + 1] ? hi : prefix[i + 1];
-        const razor_head_desc e = desc[i];
-        const int rows = rows_this_step(e, has_new);
+        razor_head_desc e = desc[i];
+        int rows = rows_this_step(e, has_new);
+        while (first + (rows + kBlockRows - 1) / kBlockRows <= lo) {   // heads without a block here
+            first += (rows + kBlockRows - 1) / kBlockRows;
+            e = desc[++i];
+            rows = rows_this_step(e, has_new);
+        }
+        const int head_end = first + (rows + kBlockRows - 1) / kBlockRows;
+        const int seg_end = hi < head_end ? hi : head_end;
         const int b = i / n_kv_heads, h = i % n_kv_heads;
-        const char *kplane = arena + e.row_off * 2 * RB;
-        const char *vplane = kplane + (int64_t)e.cap * RB;
+        char *kplane = arena + e.row_off * 2 * RB;
+        char *vplane = kplane + (int64_t)e.cap * RB;
+        if (rows > e.rows && e.rows / kBlockRows >= lo - first && e.rows / kBlockRows < seg_end - first)
+            append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
 
         bf16x8 qreg[NS];
 #pragma unroll
@@ -279,10 +333,11 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
 // probability from the lane that owns it.
 template <int D, int G, int PF>
 __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
-    const float *__restrict__ Q, const char *__restrict__ arena,
-    const razor_head_desc *__restrict__ desc, const int32_t *__restrict__ prefix,
-    float *__restrict__ part_ml, float *__restrict__ part_acc, int n_heads, int n_kv_heads, int g,
-    int has_new, float scale_log2e)
+    const float *__restrict__ Q, char *__restrict__ arena,
+    const razor_head_desc *__restrict__ desc, const char *__restrict__ k_new,
+    const char *__restrict__ v_new, int32_t *__restrict__ prefix, float *__restrict__ part_ml,
+    float *__restrict__ part_acc, int n_heads, int n_kv_heads, int g, int n_workers,
+    float scale_log2e)
 {
     constexpr int RB = D * 4;
     constexpr int NS = RB / 64;     // K loads per block
@@ -295,21 +350,31 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
     const int w = blockIdx.x * 4 + wave;
     const int kg = lane >> 4, n = lane & 15;
     const int prow = lane / LPR, piece = lane % LPR;
-    const int per = prefix[n_heads + 1], total = prefix[n_heads];
+    const int has_new = k_new != nullptr;
+    const int total = total_blocks(desc, n_heads, has_new, lane);
+    const int per = blocks_per_worker(total, n_workers);
+    if (w == 0) write_prefix(desc, n_heads, has_new, lane, per, prefix);
     int lo = w * per;
     const int hi = lo + per < total ? lo + per : total;
     if (lo >= hi) return;
-    int i = find_head(prefix, n_heads, lo, lane);
+    int i, first;
+    locate_block(desc, n_heads, has_new, lane, lo, i, first);
 
     while (lo < hi) {
-        while (prefix[i + 1] <= lo) ++i;
-        const int first = prefix[i];
-        const int seg_end = hi < prefix[i + 1] ? hi : prefix[i + 1];
-        const razor_head_desc e = desc[i];
-        const int rows = rows_this_step(e, has_new);
+        razor_head_desc e = desc[i];
+        int rows = rows_this_step(e, has_new);
+        while (first + (rows + kBlockRows - 1) / kBlockRows <= lo) {   // heads without a block here
+            first += (rows + kBlockRows - 1) / kBlockRows;
+            e = desc[++i];
+            rows = rows_this_step(e, has_new);
+        }
+        const int head_end = first + (rows + kBlockRows - 1) / kBlockRows;
+        const int seg_end = hi < head_end ? hi : head_end;
         const int b = i / n_kv_heads, h = i % n_kv_heads;
-        const char *kplane = arena + e.row_off * 2 * RB;
-        const char *vplane = kplane + (int64_t)e.cap * RB;
+        char *kplane = arena + e.row_off * 2 * RB;
+        char *vplane = kplane + (int64_t)e.cap * RB;
+        if (rows > e.rows && e.rows / kBlockRows >= lo - first && e.rows / kBlockRows < seg_end - first)
+            append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
 
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -428,79 +493,85 @@ __device__ __forceinline__ float load_q(const void *Q, int dtype, int64_t idx)
 // One workgroup per query head.  Eq.(5): the compensation token is one more softmax
 // entry with logit scale * q.khat + ln N_d and value vhat; the partial states of the
 // head's segments are merged around the common maximum in slot order.
+constexpr int kCombineThreads = 1024;
+
 template <int D>
-__global__ __launch_bounds__(256) void combine_kernel(
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(
     const void *__restrict__ Q, int q_dtype, const float *__restrict__ comp,
     razor_head_desc *__restrict__ desc, const int32_t *__restrict__ prefix,
     const float *__restrict__ part_ml, const float *__restrict__ part_acc, void *__restrict__ O,
     int out_dtype, int n_heads, int n_kv_heads, int g, int has_new, int use_comp, float scale_log2e)
 {
-    constexpr int C4 = D / 4;        // float4 columns
-    constexpr int GR = 256 / C4;     // slot groups working in parallel
-    __shared__ float red[256];
-    __shared__ float4 red4[GR][C4];
-    __shared__ float redl[GR];
-    const int tid = threadIdx.x;
+    constexpr int C4 = D / 4;                    // float4 columns
+    constexpr int GR = kCombineThreads / C4;     // slot groups working in parallel
+    constexpr int NW = kCombineThreads / 64;
+    __shared__ float s_red[NW];
+    __shared__ float4 s_acc[GR][C4];
+    __shared__ float s_den[GR];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n_q_heads = n_kv_heads * g;
     const int bj = blockIdx.x, b = bj / n_q_heads, j = bj % n_q_heads;
     const int h = j / g, n = j % g, i = b * n_kv_heads + h;
     const razor_head_desc e = desc[i];
-    const int per = prefix[n_heads + 1];
-    const int first = prefix[i], last = prefix[i + 1];
-    const int w0 = first / per;
-    const int n_slots = last > first ? (last - 1) / per - w0 + 1 : 0;
     const bool has_comp = use_comp && e.n_dropped > 0;
 
-    float part = 0.f;
-    if (has_comp && tid < D) part = load_q(Q, q_dtype, (int64_t)bj * D + tid) * comp[(size_t)i * 2 * D + tid];
-    red[tid] = part;
-    __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (tid < o) red[tid] += red[tid + o];
-        __syncthreads();
+    if (wave == 0) {   // q . khat
+        float part = 0.f;
+        if (has_comp)
+            for (int c = lane; c < D; c += 64)
+                part += load_q(Q, q_dtype, (int64_t)bj * D + c) * comp[(size_t)i * 2 * D + c];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
+        if (lane == 0) s_red[0] = part;
     }
-    const float m_comp = has_comp ? red[0] * scale_log2e + log2f((float)e.n_dropped) : kNegInf;
+    __syncthreads();
+    const int first = prefix[i], last = prefix[i + 1], per = prefix[n_heads + 1];
+    const int w0 = first / per;
+    const int n_slots = last > first ? (last - 1) / per - w0 + 1 : 0;
+    const float m_comp = has_comp ? s_red[0] * scale_log2e + log2f((float)e.n_dropped) : kNegInf;
     __syncthreads();
 
     float mx = m_comp;
-    for (int s = tid; s < n_slots; s += 256)
+    for (int s = tid; s < n_slots; s += kCombineThreads)
         mx = fmaxf(mx, part_ml[((size_t)(w0 + s + i) * g + n) * 2]);
-    red[tid] = mx;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if (lane == 0) s_red[wave] = mx;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (tid < o) red[tid] = fmaxf(red[tid], red[tid + o]);
-        __syncthreads();
-    }
-    const float M = red[0];
+    float M = s_red[0];
+#pragma unroll
+    for (int k = 1; k < NW; ++k) M = fmaxf(M, s_red[k]);
 
     const int col = tid % C4, grp = tid / C4;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-    float lsum = 0.f;
+    float den = 0.f;
     for (int s = grp; s < n_slots; s += GR) {
         const size_t slot = (size_t)(w0 + s + i) * g + n;
-        const float wgt = fast_exp2(part_ml[slot * 2] - M);
+        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + slot * 2);
         const float4 v = *reinterpret_cast<const float4 *>(part_acc + slot * D + 4 * col);
+        const float wgt = fast_exp2(ml.x - M);
         a.x += wgt * v.x; a.y += wgt * v.y; a.z += wgt * v.z; a.w += wgt * v.w;
-        lsum += wgt * part_ml[slot * 2 + 1];
+        den += wgt * ml.y;
     }
     if (grp == 0 && has_comp) {
         const float wgt = fast_exp2(m_comp - M);
         const float4 v = *reinterpret_cast<const float4 *>(comp + ((size_t)i * 2 + 1) * D + 4 * col);
         a.x += wgt * v.x; a.y += wgt * v.y; a.z += wgt * v.z; a.w += wgt * v.w;
-        lsum += wgt;
+        den += wgt;
     }
-    red4[grp][col] = a;
-    if (col == 0) redl[grp] = lsum;
+    s_acc[grp][col] = a;
+    if (col == 0) s_den[grp] = den;
     __syncthreads();
     if (grp == 0) {
-        float den = 0.f;
+        float dsum = 0.f;
         float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
         for (int k = 0; k < GR; ++k) {
-            const float4 v = red4[k][col];
+            const float4 v = s_acc[k][col];
             num.x += v.x; num.y += v.y; num.z += v.z; num.w += v.w;
-            den += redl[k];
+            dsum += s_den[k];
         }
-        const float inv = den > 0.f ? 1.f / den : 0.f;   // a head with no entry at all gives zeros
+        const float inv = dsum > 0.f ? 1.f / dsum : 0.f;   // a head with no entry at all gives zeros
         num.x *= inv; num.y *= inv; num.z *= inv; num.w *= inv;
         if (out_dtype == RAZOR_F32) {
             *reinterpret_cast<float4 *>(static_cast<float *>(O) + (int64_t)bj * D + 4 * col) = num;
@@ -512,7 +583,8 @@ __global__ __launch_bounds__(256) void combine_kernel(
             *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(O) + (int64_t)bj * D + 4 * col) = pk;
         }
     }
-    // the step is over for this head: make the appended row permanent
+    // The step is over for this head: make the appended row permanent.  No other workgroup
+    // of this kernel reads rows or flags (block positions come from `prefix`).
     if (has_new && n == 0 && tid == 0) {
         if (e.rows < e.cap) desc[i].rows = e.rows + 1;
         else desc[i].flags = e.flags | RAZOR_HEAD_OVERFLOW;
@@ -543,16 +615,16 @@ int auto_workers(int *out)
 }
 
 template <int G>
-void launch_partial_f32(int D, dim3 grid, hipStream_t s, const float *Q, const char *arena,
-                        const razor_head_desc *desc, const int32_t *prefix, float *ml, float *acc,
-                        int n_heads, int n_kv, int g, int has_new, float sl2e)
+void launch_partial_f32(int D, dim3 grid, hipStream_t s, const float *Q, char *arena,
+                        const razor_head_desc *desc, const char *kn, const char *vn, int32_t *prefix,
+                        float *ml, float *acc, int n_heads, int n_kv, int g, int workers, float sl2e)
 {
     if (D == 64)
         hipLaunchKernelGGL((decode_partial_f32_kernel<64, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
-                           prefix, ml, acc, n_heads, n_kv, g, has_new, sl2e);
+                           kn, vn, prefix, ml, acc, n_heads, n_kv, g, workers, sl2e);
     else
         hipLaunchKernelGGL((decode_partial_f32_kernel<128, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
-                           prefix, ml, acc, n_heads, n_kv, g, has_new, sl2e);
+                           kn, vn, prefix, ml, acc, n_heads, n_kv, g, workers, sl2e);
 }
 
 }  // namespace
@@ -583,7 +655,6 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int n_heads = p->batch * p->n_kv_heads, g = p->n_q_heads / p->n_kv_heads;
     const int D = p->head_dim, has_new = k_new != nullptr;
-    const int rb = D * elem_size(p->dtype);
     char *wsb = static_cast<char *>(workspace);
     int32_t *prefix = reinterpret_cast<int32_t *>(wsb + ws.prefix_off);
     float *ml = reinterpret_cast<float *>(wsb + ws.ml_off);
@@ -592,42 +663,37 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
     const char *kn = static_cast<const char *>(k_new), *vn = static_cast<const char *>(v_new);
     const float sl2e = p->scale * 1.4426950408889634f;
 
-    const dim3 pgrid(n_heads + 1);
-    if (rb == 128)
-        hipLaunchKernelGGL((prepare_kernel<128>), pgrid, dim3(64), 0, s, desc_dev, kn, vn, a, n_heads, workers, prefix);
-    else if (rb == 256)
-        hipLaunchKernelGGL((prepare_kernel<256>), pgrid, dim3(64), 0, s, desc_dev, kn, vn, a, n_heads, workers, prefix);
-    else
-        hipLaunchKernelGGL((prepare_kernel<512>), pgrid, dim3(64), 0, s, desc_dev, kn, vn, a, n_heads, workers, prefix);
-
     const dim3 grid((workers + 3) / 4);
     if (g_profile_start) RAZOR_HIP_CHECK(hipEventRecord(g_profile_start, s));
     if (p->dtype == RAZOR_BF16) {
         const uint16_t *q = static_cast<const uint16_t *>(Q);
         if (D == 128)
             hipLaunchKernelGGL((decode_partial_bf16_kernel<128, 4>), grid, dim3(256), 0, s, q, a, desc_dev,
-                               prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+                               kn, vn, prefix, ml, acc, n_heads, p->n_kv_heads, g, workers, sl2e);
         else
             hipLaunchKernelGGL((decode_partial_bf16_kernel<64, 4>), grid, dim3(256), 0, s, q, a, desc_dev,
-                               prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+                               kn, vn, prefix, ml, acc, n_heads, p->n_kv_heads, g, workers, sl2e);
     } else {
         const float *q = static_cast<const float *>(Q);
-        if (g == 1) launch_partial_f32<1>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
-        else if (g == 2) launch_partial_f32<2>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
-        else if (g <= 4) launch_partial_f32<4>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
-        else if (g <= 8) launch_partial_f32<8>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
-        else launch_partial_f32<16>(D, grid, s, q, a, desc_dev, prefix, ml, acc, n_heads, p->n_kv_heads, g, has_new, sl2e);
+#define RAZOR_F32_ARGS D, grid, s, q, a, desc_dev, kn, vn, prefix, ml, acc, n_heads, p->n_kv_heads, g, workers, sl2e
+        if (g == 1) launch_partial_f32<1>(RAZOR_F32_ARGS);
+        else if (g == 2) launch_partial_f32<2>(RAZOR_F32_ARGS);
+        else if (g <= 4) launch_partial_f32<4>(RAZOR_F32_ARGS);
+        else if (g <= 8) launch_partial_f32<8>(RAZOR_F32_ARGS);
+        else launch_partial_f32<16>(RAZOR_F32_ARGS);
+#undef RAZOR_F32_ARGS
     }
-
     if (g_profile_stop) RAZOR_HIP_CHECK(hipEventRecord(g_profile_stop, s));
 
     const dim3 cgrid(p->batch * p->n_q_heads);
     if (D == 128)
-        hipLaunchKernelGGL((combine_kernel<128>), cgrid, dim3(256), 0, s, Q, p->dtype, comp, desc_dev, prefix,
-                           ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new, p->use_comp, sl2e);
+        hipLaunchKernelGGL((combine_kernel<128>), cgrid, dim3(kCombineThreads), 0, s, Q, p->dtype, comp,
+                           desc_dev, prefix, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
+                           p->use_comp, sl2e);
     else
-        hipLaunchKernelGGL((combine_kernel<64>), cgrid, dim3(256), 0, s, Q, p->dtype, comp, desc_dev, prefix,
-                           ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new, p->use_comp, sl2e);
+        hipLaunchKernelGGL((combine_kernel<64>), cgrid, dim3(kCombineThreads), 0, s, Q, p->dtype, comp,
+                           desc_dev, prefix, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
+                           p->use_comp, sl2e);
     RAZOR_HIP_CHECK(hipGetLastError());
     return RAZOR_OK;
 }
