@@ -607,7 +607,7 @@ int auto_workers(int *out)
     if (dev != cached_dev) {
         int cus = 0;
         RAZOR_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        cached = std::min(RAZOR_MAX_WORKERS, cus * 8);   // two 4-wave workgroups per compute unit
+        cached = std::min(RAZOR_MAX_WORKERS, cus * 4);   // one wave per SIMD: measured best for streaming
         cached_dev = dev;
     }
     *out = cached;
@@ -668,10 +668,10 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
     if (p->dtype == RAZOR_BF16) {
         const uint16_t *q = static_cast<const uint16_t *>(Q);
         if (D == 128)
-            hipLaunchKernelGGL((decode_partial_bf16_kernel<128, 4>), grid, dim3(256), 0, s, q, a, desc_dev,
+            hipLaunchKernelGGL((decode_partial_bf16_kernel<128, 2>), grid, dim3(256), 0, s, q, a, desc_dev,
                                kn, vn, prefix, ml, acc, n_heads, p->n_kv_heads, g, workers, sl2e);
         else
-            hipLaunchKernelGGL((decode_partial_bf16_kernel<64, 4>), grid, dim3(256), 0, s, q, a, desc_dev,
+            hipLaunchKernelGGL((decode_partial_bf16_kernel<64, 2>), grid, dim3(256), 0, s, q, a, desc_dev,
                                kn, vn, prefix, ml, acc, n_heads, p->n_kv_heads, g, workers, sl2e);
     } else {
         const float *q = static_cast<const float *>(Q);
