@@ -1,7 +1,7 @@
 """Python binding of the razor C-ABI library (RazorAttention hot path on MI355X).
 
-The functions `razor_plan`, `razor_compress`, `razor_decode_attn` and `razor_strerror`
-carry the names and the argument order of `include/razor.h`; they only marshal
+The functions `razor_plan`, `razor_compress`, `razor_decode_attn`, `razor_profile_events`
+and `razor_strerror` carry the names and the argument order of `include/razor.h`; they only marshal
 arguments (torch tensors -> device pointers, numpy arrays -> host pointers).  Every
 step of the path runs in the HIP kernels of `librazor.so`; there is no Python or CPU
 fallback: a missing library raises on first use.
