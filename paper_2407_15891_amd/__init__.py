@@ -18,7 +18,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "librazor.so")
+LIB_PATH = os.environ.get("RAZOR_LIBRARY", os.path.join(_HERE, "librazor.so"))   # override: debug builds
 
 RAZOR_F32, RAZOR_BF16 = 0, 1
 RAZOR_OK, RAZOR_EINVAL, RAZOR_ECAPACITY, RAZOR_EHIP = 0, -1, -2, -3

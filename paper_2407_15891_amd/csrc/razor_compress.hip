@@ -3,12 +3,14 @@
 //   mean   column sums of the dropped rows [n_sink, N - window) -> khat, vhat (fp32)
 //   copy   kept rows (sinks + window, or everything) -> arena; K re-tiled through LDS
 //   index  kept positions as int32 (optional)
-// All of it is HBM streaming: every source row is read once, kept rows written once.
+// All of it is HBM streaming: every source row is read once, kept rows written once.  The
+// two streaming kernels run one wavefront per SIMD over equal shares of their rows.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <vector>
 
+#include "razor_device.h"
 #include "razor_internal.h"
 
 namespace razor {
@@ -27,9 +29,11 @@ __global__ void upload_desc_kernel(DescBatch batch, int first, int count, razor_
     if (t < count) desc[first + t] = batch.d[t];
 }
 
-__device__ __forceinline__ float bf16_bits_to_float(uint32_t lo16)
+// Source rows are read exactly once: non-temporal loads.
+__device__ __forceinline__ uint4 stream_load16(const char *p)
 {
-    return __uint_as_float(lo16 << 16);
+    const u32x4 v = stream_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
 // Adds the elements of one 16-byte piece to acc[0..NE).
@@ -41,98 +45,138 @@ __device__ __forceinline__ void accumulate_piece(const uint4 &v, float *acc)
         acc[1] += __uint_as_float(v.y);
         acc[2] += __uint_as_float(v.z);
         acc[3] += __uint_as_float(v.w);
-    } else {
-        acc[0] += bf16_bits_to_float(v.x & 0xffffu);
+    } else {   // bf16 pair per dword: low half shifted up, high half masked
+        acc[0] += __uint_as_float(v.x << 16);
         acc[1] += __uint_as_float(v.x & 0xffff0000u);
-        acc[2] += bf16_bits_to_float(v.y & 0xffffu);
+        acc[2] += __uint_as_float(v.y << 16);
         acc[3] += __uint_as_float(v.y & 0xffff0000u);
-        acc[4] += bf16_bits_to_float(v.z & 0xffffu);
+        acc[4] += __uint_as_float(v.z << 16);
         acc[5] += __uint_as_float(v.z & 0xffff0000u);
-        acc[6] += bf16_bits_to_float(v.w & 0xffffu);
+        acc[6] += __uint_as_float(v.w << 16);
         acc[7] += __uint_as_float(v.w & 0xffff0000u);
     }
 }
 
-// Eq.(4), first level.  Workgroup (slab, head) sums up to kMeanSlabRows dropped rows of
-// K and of V column-wise.  Thread t owns the 16-byte piece t % LPR of rows
-// t / LPR, t / LPR + RPP, ...; the row groups are then added in a fixed order.
+// Eq.(4), first level.  The dropped ranges of all heads form one axis of 16-row blocks, cut
+// into equal ranges, one per wavefront (same scheme as the decode kernel).  A wave streams
+// its rows once -- lane (prow, piece) owns one 16-byte piece of rows prow, prow + RPI, ... of
+// every block -- keeps fp32 column sums of K and V, adds the row groups with shuffles and
+// stores one partial sum per head segment into slot wave + head.  Fixed order throughout.
 template <int DTYPE, int D>
-__global__ __launch_bounds__(256) void mean_partial_kernel(
+__global__ __launch_bounds__(256) void mean_stream_kernel(
     const char *__restrict__ K, const char *__restrict__ V, int64_t stride_b, int64_t stride_h,
-    int64_t stride_n, const razor_head_desc *__restrict__ desc, int n_kv_heads, int n_sink,
-    int max_slabs, float *__restrict__ partial)
+    int64_t stride_n, const razor_head_desc *__restrict__ desc, int n_heads, int n_kv_heads,
+    int n_sink, int n_workers, int32_t *__restrict__ prefix, float *__restrict__ partial)
 {
     constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
     constexpr int NE = 16 / ES;        // elements per piece
-    constexpr int LPR = D * ES / 16;   // pieces (threads) per row
-    constexpr int RPP = 256 / LPR;     // rows per pass of the workgroup
-    const int head = blockIdx.y, slab = blockIdx.x;
-    const razor_head_desc e = desc[head];
-    const int64_t lo = (int64_t)n_sink + (int64_t)slab * kMeanSlabRows;
-    const int64_t d_hi = (int64_t)n_sink + e.n_dropped;
-    if (e.n_dropped <= 0 || lo >= d_hi) return;
-    const int64_t hi = lo + kMeanSlabRows < d_hi ? lo + kMeanSlabRows : d_hi;
-    const int b = head / n_kv_heads, h = head % n_kv_heads;
-    const int64_t base = (b * stride_b + h * stride_h) * ES;
-    const int piece = threadIdx.x % LPR, rgrp = threadIdx.x / LPR;
+    constexpr int LPR = D * ES / 16;   // lanes per row
+    constexpr int RPI = 64 / LPR;      // rows one wave-wide load covers
+    constexpr int NI = kBlockRows / RPI;
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int prow = lane / LPR, piece = lane % LPR;
+    const DroppedBlocks count;
+    const int total = total_blocks(count, desc, n_heads, lane);
+    const int per = blocks_per_worker(total, n_workers);
+    if (w == 0) write_prefix(count, desc, n_heads, lane, per, prefix);
+    int lo = w * per;
+    const int hi = lo + per < total ? lo + per : total;
+    if (lo >= hi) return;
+    int i, first;
+    locate_block(count, desc, n_heads, lane, lo, i, first);
 
-    float ak[NE], av[NE];
+    while (lo < hi) {
+        razor_head_desc e = desc[i];
+        while (first + (e.n_dropped + kBlockRows - 1) / kBlockRows <= lo) {
+            first += (e.n_dropped + kBlockRows - 1) / kBlockRows;
+            e = desc[++i];
+        }
+        const int head_end = first + (e.n_dropped + kBlockRows - 1) / kBlockRows;
+        const int seg_end = hi < head_end ? hi : head_end;
+        const int b = i / n_kv_heads, h = i % n_kv_heads;
+        const int64_t base = (b * stride_b + h * stride_h) * ES + piece * 16;
+        const int64_t row_bytes = stride_n * ES;
+        const int d_lo = n_sink, d_hi = n_sink + e.n_dropped;
+
+        float ak[NE], av[NE];
 #pragma unroll
-    for (int i = 0; i < NE; ++i) ak[i] = av[i] = 0.f;
-    int64_t r = lo + rgrp;
-    for (; r + 3 * RPP < hi; r += 4 * RPP) {   // four rows in flight per thread
-        uint4 k4[4], v4[4];
+        for (int c = 0; c < NE; ++c) ak[c] = av[c] = 0.f;
+        uint4 kb[2][NI], vb[2][NI];
+        auto load_block = [&](int t, uint4(&k)[NI], uint4(&v)[NI]) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t off = base + (r + u * RPP) * stride_n * ES + piece * 16;
-            k4[u] = *reinterpret_cast<const uint4 *>(K + off);
-            v4[u] = *reinterpret_cast<const uint4 *>(V + off);
+            for (int r = 0; r < NI; ++r) {
+                int row = d_lo + t * kBlockRows + r * RPI + prow;
+                const bool valid = row < d_hi;
+                row = valid ? row : d_hi - 1;
+                k[r] = stream_load16(K + base + row * row_bytes);
+                v[r] = stream_load16(V + base + row * row_bytes);
+                if (!valid) k[r] = v[r] = make_uint4(0, 0, 0, 0);   // +0.0 in either format
+            }
+        };
+        auto add_block = [&](const uint4(&k)[NI], const uint4(&v)[NI]) {
+#pragma unroll
+            for (int r = 0; r < NI; ++r) {
+                accumulate_piece<DTYPE>(k[r], ak);
+                accumulate_piece<DTYPE>(v[r], av);
+            }
+        };
+        const int t0 = lo - first, t1 = seg_end - first;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            if (t0 + u < t1) load_block(t0 + u, kb[u], vb[u]);
+        for (int t = t0; t < t1; t += 2) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                if (t + u < t1) {
+                    add_block(kb[u], vb[u]);
+                    if (t + u + 2 < t1) load_block(t + u + 2, kb[u], vb[u]);
+                }
+            }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            accumulate_piece<DTYPE>(k4[u], ak);
-            accumulate_piece<DTYPE>(v4[u], av);
-        }
-    }
-    for (; r < hi; r += RPP) {
-        const int64_t off = base + r * stride_n * ES + piece * 16;
-        accumulate_piece<DTYPE>(*reinterpret_cast<const uint4 *>(K + off), ak);
-        accumulate_piece<DTYPE>(*reinterpret_cast<const uint4 *>(V + off), av);
-    }
-
-    __shared__ float red[2][RPP][D + 4];
+        for (int c = 0; c < NE; ++c) {
 #pragma unroll
-    for (int i = 0; i < NE; ++i) {
-        red[0][rgrp][piece * NE + i] = ak[i];
-        red[1][rgrp][piece * NE + i] = av[i];
-    }
-    __syncthreads();
-    for (int t = threadIdx.x; t < 2 * D; t += 256) {
-        const int which = t / D, c = t % D;
-        float s = 0.f;
-        for (int g = 0; g < RPP; ++g) s += red[which][g][c];
-        partial[(((size_t)head * max_slabs + slab) * 2 + which) * D + c] = s;
+            for (int o = LPR; o < 64; o <<= 1) {
+                ak[c] += __shfl_xor(ak[c], o);
+                av[c] += __shfl_xor(av[c], o);
+            }
+        }
+        if (prow == 0) {
+            float *dst = partial + (size_t)(w + i) * 2 * D + piece * NE;
+#pragma unroll
+            for (int c = 0; c < NE; ++c) {
+                dst[c] = ak[c];
+                dst[D + c] = av[c];
+            }
+        }
+        lo = seg_end;
     }
 }
 
-// Eq.(4), second level: add the slab sums in order (double keeps the tail exact enough
-// that the result does not depend on the slab size) and divide by N_d.
+// Eq.(4), second level: add the segment sums of a head (four interleaved groups, each in
+// slot order, then the groups in order; double keeps the result independent of how the rows
+// were cut) and divide by N_d.  blockDim = (2 * D, 4).
 template <int D>
-__global__ void mean_final_kernel(const razor_head_desc *__restrict__ desc, int max_slabs,
+__global__ void mean_final_kernel(const razor_head_desc *__restrict__ desc, int n_heads,
+                                  const int32_t *__restrict__ prefix,
                                   const float *__restrict__ partial, float *__restrict__ comp)
 {
-    const int head = blockIdx.x;
-    const razor_head_desc e = desc[head];
-    for (int t = threadIdx.x; t < 2 * D; t += blockDim.x) {
-        float out = 0.f;
-        if (e.n_dropped > 0) {
-            const int slabs = (e.n_dropped + kMeanSlabRows - 1) / kMeanSlabRows;
-            double s = 0.0;
-            for (int k = 0; k < slabs; ++k)
-                s += (double)partial[((size_t)head * max_slabs + k) * 2 * D + t];
-            out = (float)(s / (double)e.n_dropped);
-        }
-        comp[(size_t)head * 2 * D + t] = out;
+    __shared__ double red[4][2 * D];
+    const int head = blockIdx.x, t = threadIdx.x, grp = threadIdx.y;
+    const int n_dropped = desc[head].n_dropped;
+    double s = 0.0;
+    if (n_dropped > 0) {
+        const int first = prefix[head], last = prefix[head + 1], per = prefix[n_heads + 1];
+        const int w0 = first / per, n_slots = (last - 1) / per - w0 + 1;
+        for (int k = grp; k < n_slots; k += 4)
+            s += (double)partial[(size_t)(w0 + k + head) * 2 * D + t];
+    }
+    red[grp][t] = s;
+    __syncthreads();
+    if (grp == 0) {
+        const double sum = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+        comp[(size_t)head * 2 * D + t] = n_dropped > 0 ? (float)(sum / (double)n_dropped) : 0.f;
     }
 }
 
@@ -143,54 +187,78 @@ __device__ __forceinline__ int64_t source_row(int t, const razor_head_desc &e, i
     return (e.n_dropped > 0 && t >= n_sink) ? (int64_t)t + e.n_dropped : (int64_t)t;
 }
 
-// Compaction (Algorithm 1 step 3).  One wavefront moves one 16-row block: V rows are
-// copied as they are; K rows are read row-major (coalesced), staged in LDS and written
+// Compaction (Algorithm 1 step 3).  The kept rows of all heads form one axis of 16-row
+// destination blocks, cut into equal ranges, one per wavefront.  Per block: V rows are copied
+// as they are; K rows are read row-major (coalesced), staged in wave-private LDS and written
 // back piece-major, the layout the decode kernel loads straight into matrix-core operands.
-// Rows past `rows` inside the last block are written as zeros.
+// Rows past `rows` inside a head's last block are written as zeros.
 template <int RB>   // bytes per row
-__global__ __launch_bounds__(256) void compact_kernel(
+__global__ __launch_bounds__(256) void compact_stream_kernel(
     const char *__restrict__ K, const char *__restrict__ V, int64_t stride_b_bytes,
     int64_t stride_h_bytes, int64_t stride_n_bytes, const razor_head_desc *__restrict__ desc,
-    int n_kv_heads, int n_sink, char *__restrict__ arena)
+    int n_heads, int n_kv_heads, int n_sink, int n_workers, char *__restrict__ arena)
 {
     constexpr int LPR = RB / 16;       // 16-byte pieces per row
     constexpr int RPI = 64 / LPR;      // rows one wave-wide load covers
-    constexpr int NI = 16 / RPI;       // loads per block
-    const int head = blockIdx.y;
-    const razor_head_desc e = desc[head];
+    constexpr int NI = kBlockRows / RPI;
+    __shared__ uint4 stage[4][kBlockRows * LPR];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int blk = blockIdx.x * 4 + wave;
-    const int n_blocks = (e.rows + kBlockRows - 1) / kBlockRows;
-    if (blk >= n_blocks) return;       // wave-private work below: no workgroup barrier
-    const int b = head / n_kv_heads, h = head % n_kv_heads;
-    const int64_t src_base = b * stride_b_bytes + h * stride_h_bytes;
-    char *kplane = arena + e.row_off * 2 * RB;
-    char *vplane = kplane + (int64_t)e.cap * RB;
-
-    __shared__ uint4 stage[4][16 * LPR];
+    const int w = blockIdx.x * 4 + wave;
     const int prow = lane / LPR, piece = lane % LPR;
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int r = i * RPI + prow;                 // row inside the block
-        const int t = blk * kBlockRows + r;           // cache row
-        uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-        if (t < e.rows) {
-            const int64_t off = src_base + source_row(t, e, n_sink) * stride_n_bytes + piece * 16;
-            kv = *reinterpret_cast<const uint4 *>(K + off);
-            vv = *reinterpret_cast<const uint4 *>(V + off);
+    const CachedBlocks count{0};
+    const int total = total_blocks(count, desc, n_heads, lane);
+    const int per = blocks_per_worker(total, n_workers);
+    int lo = w * per;
+    const int hi = lo + per < total ? lo + per : total;
+    if (lo >= hi) return;              // wave-private work below: no workgroup barrier
+    int i, first;
+    locate_block(count, desc, n_heads, lane, lo, i, first);
+
+    while (lo < hi) {
+        razor_head_desc e = desc[i];
+        while (first + (e.rows + kBlockRows - 1) / kBlockRows <= lo) {
+            first += (e.rows + kBlockRows - 1) / kBlockRows;
+            e = desc[++i];
         }
-        *reinterpret_cast<uint4 *>(vplane + (int64_t)t * RB + piece * 16) = vv;
-        stage[wave][r * LPR + (piece ^ (r % LPR))] = kv;   // xor keeps the column reads conflict-free
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    char *kblock = kplane + (int64_t)blk * kBlockRows * RB;
+        const int head_end = first + (e.rows + kBlockRows - 1) / kBlockRows;
+        const int seg_end = hi < head_end ? hi : head_end;
+        const int b = i / n_kv_heads, h = i % n_kv_heads;
+        const int64_t src_base = b * stride_b_bytes + h * stride_h_bytes + piece * 16;
+        char *kplane = arena + e.row_off * 2 * RB;
+        char *vplane = kplane + (int64_t)e.cap * RB;
+
+        for (int blk = lo - first; blk < seg_end - first; ++blk) {
+            uint4 kv[NI], vv[NI];
 #pragma unroll
-    for (int s = 0; s < NI; ++s) {
-        const int pos = s * 64 + lane;                // 16-byte slot inside the block
-        const int c = pos / 16, r = pos % 16;         // piece-major: slot = c * 16 + r
-        *reinterpret_cast<uint4 *>(kblock + (int64_t)pos * 16) = stage[wave][r * LPR + (c ^ (r % LPR))];
+            for (int r = 0; r < NI; ++r) {
+                const int t = blk * kBlockRows + r * RPI + prow;   // cache row
+                const bool valid = t < e.rows;
+                const int64_t off = src_base + source_row(valid ? t : e.rows - 1, e, n_sink) * stride_n_bytes;
+                kv[r] = stream_load16(K + off);
+                vv[r] = stream_load16(V + off);
+                if (!valid) kv[r] = vv[r] = make_uint4(0, 0, 0, 0);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // previous block's LDS reads are done
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int r = 0; r < NI; ++r) {
+                const int row = r * RPI + prow;
+                const int t = blk * kBlockRows + row;
+                *reinterpret_cast<uint4 *>(vplane + (int64_t)t * RB + piece * 16) = vv[r];
+                stage[wave][row * LPR + (piece ^ (row % LPR))] = kv[r];   // xor: conflict-free column reads
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            char *kblock = kplane + (int64_t)blk * kBlockRows * RB;
+#pragma unroll
+            for (int s = 0; s < NI; ++s) {
+                const int pos = s * 64 + lane;                // 16-byte slot inside the block
+                const int c = pos / 16, r = pos % 16;         // piece-major: slot = c * 16 + r
+                *reinterpret_cast<uint4 *>(kblock + (int64_t)pos * 16) = stage[wave][r * LPR + (c ^ (r % LPR))];
+            }
+        }
+        lo = seg_end;
     }
 }
 
@@ -212,10 +280,10 @@ template <int DTYPE, int D>
 int launch_compress(const razor_params &p, const char *K, const char *V, int64_t stride_b,
                     int64_t stride_h, int64_t stride_n, const std::vector<razor_head_desc> &desc,
                     int max_dropped, char *arena, float *comp, razor_head_desc *desc_dev,
-                    int32_t *kept_idx_dev, float *partial, hipStream_t stream)
+                    int32_t *kept_idx_dev, int32_t *prefix, float *partial, int workers,
+                    hipStream_t stream)
 {
     constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
-    constexpr int RB = D * ES;
     const int n_heads = (int)desc.size();
     for (int first = 0; first < n_heads; first += kDescPerLaunch) {
         DescBatch batch;
@@ -225,28 +293,23 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
         hipLaunchKernelGGL(upload_desc_kernel, dim3(1), dim3(kDescPerLaunch), 0, stream, batch,
                            first, count, desc_dev);
     }
-    const int max_slabs = compress_workspace(p, max_dropped).max_slabs;
-    if (max_slabs > 0) {
-        hipLaunchKernelGGL((mean_partial_kernel<DTYPE, D>), dim3(max_slabs, n_heads), dim3(256), 0,
-                           stream, K, V, stride_b, stride_h, stride_n, desc_dev, p.n_kv_heads,
-                           p.n_sink, max_slabs, partial);
-    }
-    hipLaunchKernelGGL((mean_final_kernel<D>), dim3(n_heads), dim3(2 * D), 0, stream, desc_dev,
-                       max_slabs, partial, comp);
-    int max_blocks = 0, max_rows = 0;
-    for (const razor_head_desc &e : desc) {
-        max_rows = std::max(max_rows, e.rows);
-        max_blocks = std::max(max_blocks, (e.rows + kBlockRows - 1) / kBlockRows);
-    }
-    if (max_blocks > 0) {
-        hipLaunchKernelGGL((compact_kernel<RB>), dim3((max_blocks + 3) / 4, n_heads), dim3(256), 0,
-                           stream, K, V, stride_b * ES, stride_h * ES, stride_n * ES, desc_dev,
-                           p.n_kv_heads, p.n_sink, arena);
-        if (kept_idx_dev) {
-            const int gx = std::min((max_rows + 255) / 256, 64);
-            hipLaunchKernelGGL(kept_index_kernel, dim3(gx, n_heads), dim3(256), 0, stream, desc_dev,
-                               p.n_sink, kept_idx_dev);
-        }
+    int max_rows = 0;
+    for (const razor_head_desc &e : desc) max_rows = std::max(max_rows, e.rows);
+    const dim3 grid((workers + 3) / 4);
+    if (max_dropped > 0)
+        hipLaunchKernelGGL((mean_stream_kernel<DTYPE, D>), grid, dim3(256), 0, stream, K, V, stride_b,
+                           stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads, p.n_sink, workers,
+                           prefix, partial);
+    hipLaunchKernelGGL((mean_final_kernel<D>), dim3(n_heads), dim3(2 * D, 4), 0, stream, desc_dev,
+                       n_heads, prefix, partial, comp);
+    if (max_rows > 0)
+        hipLaunchKernelGGL((compact_stream_kernel<D * ES>), grid, dim3(256), 0, stream, K, V,
+                           stride_b * ES, stride_h * ES, stride_n * ES, desc_dev, n_heads,
+                           p.n_kv_heads, p.n_sink, workers, arena);
+    if (kept_idx_dev && max_rows > 0) {
+        const int gx = std::min((max_rows + 255) / 256, 64);
+        hipLaunchKernelGGL(kept_index_kernel, dim3(gx, n_heads), dim3(256), 0, stream, desc_dev,
+                           p.n_sink, kept_idx_dev);
     }
     RAZOR_HIP_CHECK(hipGetLastError());
     return RAZOR_OK;
@@ -278,16 +341,23 @@ extern "C" int razor_compress(const razor_params *p, const void *K, const void *
     int rc = build_plan(*p, seq_lens_host, retrieval_mask_host, desc, sizes, max_dropped);
     if (rc != RAZOR_OK) return rc;
     if (sizes.arena_bytes > 0 && !arena) return RAZOR_EINVAL;
-    const CompressWorkspace ws = compress_workspace(*p, max_dropped);
-    if (ws.bytes > 0 && (!workspace || workspace_bytes < ws.bytes)) return RAZOR_ECAPACITY;
+    const CompressWorkspace ws = compress_workspace(*p);
+    if (!workspace || workspace_bytes < ws.bytes) return RAZOR_ECAPACITY;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const char *k = static_cast<const char *>(K), *v = static_cast<const char *>(V);
     char *a = static_cast<char *>(arena);
+    int32_t *prefix = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + ws.prefix_off);
     float *partial = reinterpret_cast<float *>(static_cast<char *>(workspace) + ws.partial_off);
+    int workers = p->n_workers;
+    if (workers == 0) {
+        rc = auto_workers(&workers);
+        if (rc != RAZOR_OK) return rc;
+    }
+    workers = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
 #define RAZOR_DISPATCH(DT, DD)                                                                    \
     return launch_compress<DT, DD>(*p, k, v, stride_b, stride_h, stride_n, desc, max_dropped, a,  \
-                                   comp, desc_dev, kept_idx_dev, partial, s)
+                                   comp, desc_dev, kept_idx_dev, prefix, partial, workers, s)
     if (p->dtype == RAZOR_BF16 && p->head_dim == 128) RAZOR_DISPATCH(RAZOR_BF16, 128);
     if (p->dtype == RAZOR_BF16 && p->head_dim == 64) RAZOR_DISPATCH(RAZOR_BF16, 64);
     if (p->dtype == RAZOR_F32 && p->head_dim == 128) RAZOR_DISPATCH(RAZOR_F32, 128);

@@ -24,6 +24,7 @@
 #include <cmath>
 #include <type_traits>
 
+#include "razor_device.h"
 #include "razor_internal.h"
 
 namespace razor {
@@ -31,18 +32,8 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kNegInf = -__builtin_huge_valf();
-
-// Cache rows are read once per step and never again before the whole cache has gone by:
-// non-temporal loads keep them from displacing each other in L2 and measurably raise the
-// streaming rate.
-template <typename T>
-__device__ __forceinline__ T stream_load(const T *p) { return __builtin_nontemporal_load(p); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -53,89 +44,21 @@ __device__ __forceinline__ int rows_this_step(const razor_head_desc &e, int has_
     return e.rows + ((has_new && e.rows < e.cap) ? 1 : 0);
 }
 
-// ---------------------------------------------------------------- the flattened block axis
-__device__ __forceinline__ int wave_sum(int v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-
-// 16-row blocks head idx holds this step (0 for idx >= n_heads).
-__device__ __forceinline__ int head_blocks(const razor_head_desc *__restrict__ desc, int idx,
-                                           int n_heads, int has_new)
-{
-    if (idx >= n_heads) return 0;
-    const int2 rc = *reinterpret_cast<const int2 *>(reinterpret_cast<const char *>(desc + idx) + 16);
-    const int rows = rc.x + ((has_new && rc.x < rc.y) ? 1 : 0);   // {rows, cap}
-    return (rows + kBlockRows - 1) / kBlockRows;
-}
-
-// Blocks per worker for this step: the flattened axis cut into n_workers equal ranges.
-__device__ __forceinline__ int blocks_per_worker(int total, int n_workers)
-{
-    const int per = (total + n_workers - 1) / n_workers;
-    return per < kMinBlocksPerWorker ? kMinBlocksPerWorker : per;
-}
-
-// Wave-cooperative.  Sum of head_blocks over all heads.
-__device__ __forceinline__ int total_blocks(const razor_head_desc *__restrict__ desc, int n_heads,
-                                            int has_new, int lane)
-{
-    int acc = 0;
-    for (int base = 0; base < n_heads; base += 64) acc += head_blocks(desc, base + lane, n_heads, has_new);
-    return wave_sum(acc);
-}
-
-// Wave-cooperative.  The head that owns flattened block `blk` (< total) and the flattened
-// index of that head's first block.
-__device__ __forceinline__ void locate_block(const razor_head_desc *__restrict__ desc, int n_heads,
-                                             int has_new, int lane, int blk, int &head, int &first)
-{
-    int carry = 0;
-    head = 0;
-    first = 0;
-    for (int base = 0; base < n_heads; base += 64) {
-        int incl = head_blocks(desc, base + lane, n_heads, has_new);
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int up = __shfl_up(incl, o);
-            if (lane >= o) incl += up;
-        }
-        const int end = carry + incl;                      // flattened end of head base + lane
-        const int c = __popcll(__ballot(end <= blk));      // ends are non-decreasing
-        if (c < 64) {
-            head = base + c;
-            first = c == 0 ? carry : __shfl(end, c - 1);
-            return;
-        }
-        carry = __shfl(end, 63);
+// Debug builds (-DRAZOR_TIMELINE) stamp the 100 MHz wall clock at a few points of every
+// streaming wave and drop the stamps behind the last partial slot; off in the product.
+#ifdef RAZOR_TIMELINE
+#define RAZOR_STAMP(k) long long stamp_##k = wall_clock64()
+#define RAZOR_STAMP_SEG() ++stamp_segments
+#define RAZOR_STAMP_FLUSH()                                                                        \
+    if (lane == 0) {                                                                               \
+        long long *dst = reinterpret_cast<long long *>(part_acc + (size_t)7000 * g * (RB / 2)) + (size_t)w * 4; \
+        dst[0] = stamp_0; dst[1] = stamp_1; dst[2] = stamp_2; dst[3] = stamp_segments;             \
     }
-}
-
-// Wave-cooperative.  prefix[i] = flattened index of head i's first block, prefix[n_heads] =
-// total, prefix[n_heads + 1] = blocks per worker: what the combine kernel needs to find the
-// partial states of a head.
-__device__ __forceinline__ void write_prefix(const razor_head_desc *__restrict__ desc, int n_heads,
-                                             int has_new, int lane, int per,
-                                             int32_t *__restrict__ prefix)
-{
-    int carry = 0;
-    for (int base = 0; base < n_heads; base += 64) {
-        int incl = head_blocks(desc, base + lane, n_heads, has_new);
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int up = __shfl_up(incl, o);
-            if (lane >= o) incl += up;
-        }
-        if (base + lane < n_heads) prefix[base + lane + 1] = carry + incl;
-        carry += __shfl(incl, 63);
-    }
-    if (lane == 0) {
-        prefix[0] = 0;
-        prefix[n_heads + 1] = per;
-    }
-}
+#else
+#define RAZOR_STAMP(k)
+#define RAZOR_STAMP_SEG()
+#define RAZOR_STAMP_FLUSH()
+#endif
 
 // The new token of head `head` goes to row e.rows of its planes (K piece-major inside its
 // block, V row-major).  Called by the one wave whose range holds that row's block.
@@ -189,14 +112,20 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
     const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int kg = lane >> 4, n = lane & 15;
     const int has_new = k_new != nullptr;
-    const int total = total_blocks(desc, n_heads, has_new, lane);
+#ifdef RAZOR_TIMELINE
+    long long stamp_segments = 0;
+#endif
+    RAZOR_STAMP(0);
+    const CachedBlocks count{has_new};
+    const int total = total_blocks(count, desc, n_heads, lane);
     const int per = blocks_per_worker(total, n_workers);
-    if (w == 0) write_prefix(desc, n_heads, has_new, lane, per, prefix);
+    if (w == 0) write_prefix(count, desc, n_heads, lane, per, prefix);
     int lo = w * per;
     const int hi = lo + per < total ? lo + per : total;
     if (lo >= hi) return;
     int i, first;
-    locate_block(desc, n_heads, has_new, lane, lo, i, first);
+    locate_block(count, desc, n_heads, lane, lo, i, first);
+    RAZOR_STAMP(1);
 
     while (lo < hi) {
         razor_head_desc e = desc[i];
@@ -322,7 +251,10 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
             }
         }
         lo = seg_end;
+        RAZOR_STAMP_SEG();
     }
+    RAZOR_STAMP(2);
+    RAZOR_STAMP_FLUSH();
 }
 
 // ---------------------------------------------------------------- partial, fp32 / vector ALU
@@ -351,14 +283,20 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
     const int kg = lane >> 4, n = lane & 15;
     const int prow = lane / LPR, piece = lane % LPR;
     const int has_new = k_new != nullptr;
-    const int total = total_blocks(desc, n_heads, has_new, lane);
+#ifdef RAZOR_TIMELINE
+    long long stamp_segments = 0;
+#endif
+    RAZOR_STAMP(0);
+    const CachedBlocks count{has_new};
+    const int total = total_blocks(count, desc, n_heads, lane);
     const int per = blocks_per_worker(total, n_workers);
-    if (w == 0) write_prefix(desc, n_heads, has_new, lane, per, prefix);
+    if (w == 0) write_prefix(count, desc, n_heads, lane, per, prefix);
     int lo = w * per;
     const int hi = lo + per < total ? lo + per : total;
     if (lo >= hi) return;
     int i, first;
-    locate_block(desc, n_heads, has_new, lane, lo, i, first);
+    locate_block(count, desc, n_heads, lane, lo, i, first);
+    RAZOR_STAMP(1);
 
     while (lo < hi) {
         razor_head_desc e = desc[i];
@@ -480,7 +418,10 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
             }
         }
         lo = seg_end;
+        RAZOR_STAMP_SEG();
     }
+    RAZOR_STAMP(2);
+    RAZOR_STAMP_FLUSH();
 }
 
 // ---------------------------------------------------------------- combine
@@ -598,21 +539,6 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
     } while (0)
 
 thread_local hipEvent_t g_profile_start = nullptr, g_profile_stop = nullptr;
-
-int auto_workers(int *out)
-{
-    static thread_local int cached_dev = -1, cached = 0;
-    int dev = 0;
-    RAZOR_HIP_CHECK(hipGetDevice(&dev));
-    if (dev != cached_dev) {
-        int cus = 0;
-        RAZOR_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        cached = std::min(RAZOR_MAX_WORKERS, cus * 4);   // one wave per SIMD: measured best for streaming
-        cached_dev = dev;
-    }
-    *out = cached;
-    return RAZOR_OK;
-}
 
 template <int G>
 void launch_partial_f32(int D, dim3 grid, hipStream_t s, const float *Q, char *arena,

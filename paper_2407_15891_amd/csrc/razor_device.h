@@ -1,0 +1,121 @@
+// Device-side helpers shared by the streaming kernels: the ragged per-head length table
+// flattened into one axis of 16-row blocks, cut into equal ranges, one per wavefront.
+// Every wave derives its range from the descriptor table alone (one coalesced load per 64
+// heads plus wave scans), so no launch has to precede the streaming kernels.
+#ifndef RAZOR_DEVICE_H
+#define RAZOR_DEVICE_H
+
+#include <hip/hip_runtime.h>
+
+#include "razor_internal.h"
+
+namespace razor {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Cache and source rows are read once per pass and not again before everything else has
+// gone by: non-temporal loads keep them from displacing each other in L2 and measurably
+// raise the streaming rate.
+template <typename T>
+__device__ __forceinline__ T stream_load(const T *p) { return __builtin_nontemporal_load(p); }
+
+__device__ __forceinline__ int wave_sum(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(v, o);
+        if (lane >= o) v += up;
+    }
+    return v;
+}
+
+// How many 16-row blocks a head contributes to the axis being streamed.
+struct CachedBlocks {   // rows held this decode step (the token being appended included)
+    int has_new;
+    __device__ __forceinline__ int operator()(const razor_head_desc *__restrict__ desc, int idx) const
+    {
+        const int2 rc = *reinterpret_cast<const int2 *>(reinterpret_cast<const char *>(desc + idx) + 16);
+        const int rows = rc.x + ((has_new && rc.x < rc.y) ? 1 : 0);   // {rows, cap}
+        return (rows + kBlockRows - 1) / kBlockRows;
+    }
+};
+struct DroppedBlocks {  // rows Eq.(4) averages
+    __device__ __forceinline__ int operator()(const razor_head_desc *__restrict__ desc, int idx) const
+    {
+        const int nd = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(desc + idx) + 24);
+        return (nd + kBlockRows - 1) / kBlockRows;
+    }
+};
+
+// The flattened axis cut into n_workers equal ranges.
+__device__ __forceinline__ int blocks_per_worker(int total, int n_workers)
+{
+    const int per = (total + n_workers - 1) / n_workers;
+    return per < kMinBlocksPerWorker ? kMinBlocksPerWorker : per;
+}
+
+// Wave-cooperative.  Length of the axis.
+template <class F>
+__device__ __forceinline__ int total_blocks(F count, const razor_head_desc *__restrict__ desc,
+                                            int n_heads, int lane)
+{
+    int acc = 0;
+    for (int base = 0; base < n_heads; base += 64)
+        if (base + lane < n_heads) acc += count(desc, base + lane);
+    return wave_sum(acc);
+}
+
+// Wave-cooperative.  The head that owns flattened block `blk` (< total) and the flattened
+// index of that head's first block.
+template <class F>
+__device__ __forceinline__ void locate_block(F count, const razor_head_desc *__restrict__ desc,
+                                             int n_heads, int lane, int blk, int &head, int &first)
+{
+    int carry = 0;
+    head = 0;
+    first = 0;
+    for (int base = 0; base < n_heads; base += 64) {
+        const int nb = base + lane < n_heads ? count(desc, base + lane) : 0;
+        const int end = carry + wave_inclusive_scan(nb, lane);   // flattened end of head base + lane
+        const int c = __popcll(__ballot(end <= blk));             // ends are non-decreasing
+        if (c < 64) {
+            head = base + c;
+            first = c == 0 ? carry : __shfl(end, c - 1);
+            return;
+        }
+        carry = __shfl(end, 63);
+    }
+}
+
+// Wave-cooperative.  prefix[i] = flattened index of head i's first block, prefix[n_heads] =
+// length of the axis, prefix[n_heads + 1] = blocks per worker: what a later kernel needs to
+// find the partial results of a head (segment of worker w in head i -> slot w + i).
+template <class F>
+__device__ __forceinline__ void write_prefix(F count, const razor_head_desc *__restrict__ desc,
+                                             int n_heads, int lane, int per,
+                                             int32_t *__restrict__ prefix)
+{
+    int carry = 0;
+    for (int base = 0; base < n_heads; base += 64) {
+        const int nb = base + lane < n_heads ? count(desc, base + lane) : 0;
+        const int incl = wave_inclusive_scan(nb, lane);
+        if (base + lane < n_heads) prefix[base + lane + 1] = carry + incl;
+        carry += __shfl(incl, 63);
+    }
+    if (lane == 0) {
+        prefix[0] = 0;
+        prefix[n_heads + 1] = per;
+    }
+}
+
+}  // namespace razor
+#endif

@@ -11,7 +11,6 @@
 namespace razor {
 
 constexpr int kBlockRows = RAZOR_BLOCK_ROWS;  // K rows per arena block
-constexpr int kMeanSlabRows = 1024;           // dropped rows one workgroup sums (Eq.(4))
 constexpr int kMinBlocksPerWorker = 2;        // never split a decode finer than this
 
 inline int elem_size(int dtype) { return dtype == RAZOR_F32 ? 4 : 2; }
@@ -29,11 +28,14 @@ struct DecodeWorkspace {
 DecodeWorkspace decode_workspace(const razor_params &p);
 
 struct CompressWorkspace {
-    size_t partial_off;  // float[n_heads][max_slabs][2][head_dim]
+    size_t prefix_off;   // int32[n_heads + 2]: dropped-block prefix sums, then blocks-per-worker
+    size_t partial_off;  // float[slots][2][head_dim]: column sums per (worker, head) segment
     size_t bytes;
-    int max_slabs;
 };
-CompressWorkspace compress_workspace(const razor_params &p, int max_dropped);
+CompressWorkspace compress_workspace(const razor_params &p);
+
+// Wavefronts a streaming launch is split over on the current device (one per SIMD).
+int auto_workers(int *out);
 
 // Validates p; returns RAZOR_OK or RAZOR_EINVAL.
 int check_params(const razor_params *p);

@@ -49,14 +49,31 @@ DecodeWorkspace decode_workspace(const razor_params &p)
     return w;
 }
 
-CompressWorkspace compress_workspace(const razor_params &p, int max_dropped)
+CompressWorkspace compress_workspace(const razor_params &p)
 {
     const size_t n_heads = (size_t)p.batch * p.n_kv_heads;
     CompressWorkspace w;
-    w.max_slabs = (max_dropped + kMeanSlabRows - 1) / kMeanSlabRows;
-    w.partial_off = 0;
-    w.bytes = n_heads * (size_t)w.max_slabs * 2 * p.head_dim * sizeof(float);
+    w.prefix_off = 0;
+    w.partial_off = round_up((n_heads + 2) * sizeof(int32_t), 256);
+    w.bytes = w.partial_off + (RAZOR_MAX_WORKERS + n_heads) * 2 * p.head_dim * sizeof(float);
     return w;
+}
+
+int auto_workers(int *out)
+{
+    static thread_local int cached_dev = -1, cached = 0;
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return hip_failure("hipGetDevice", (int)err);
+    if (dev != cached_dev) {
+        int cus = 0;
+        err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (err != hipSuccess) return hip_failure("hipDeviceGetAttribute", (int)err);
+        cached = cus * 4 < RAZOR_MAX_WORKERS ? cus * 4 : RAZOR_MAX_WORKERS;   // one wave per SIMD: measured best for streaming
+        cached_dev = dev;
+    }
+    *out = cached;
+    return RAZOR_OK;
 }
 
 int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *mask,
@@ -94,7 +111,7 @@ int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *ma
     sizes.comp_bytes = (uint64_t)n_heads * 2 * p.head_dim * sizeof(float);
     sizes.desc_bytes = (uint64_t)n_heads * sizeof(razor_head_desc);
     sizes.kept_idx_bytes = (uint64_t)kept_off * sizeof(int32_t);
-    const size_t wd = decode_workspace(p).bytes, wc = compress_workspace(p, max_dropped).bytes;
+    const size_t wd = decode_workspace(p).bytes, wc = compress_workspace(p).bytes;
     sizes.workspace_bytes = round_up(wd > wc ? wd : wc, 256);
     sizes.total_rows = kept_off;
     sizes.total_cap = row_off;
