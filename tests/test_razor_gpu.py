@@ -279,3 +279,41 @@ def test_full_size_config4():
     np.testing.assert_array_equal(desc["rows"], oc.rows().reshape(-1))
     np.testing.assert_array_equal(desc["n_dropped"], oc.N_d.reshape(-1))
     run_steps(w, cache, oc, 1, "config 4")
+
+
+def test_full_size_config5_sampled_layers():
+    """Config 5: layers of the 32-layer stack are independent here (attention only), so a
+    sample of layers covering every retrieval pattern (0, 1, 2, 3 retrieval KV heads) is run
+    through all 256 decode steps; the oracle checks steps 0, 127 and 255 of every
+    (sequence, head) of those layers: 3 steps x 8 sequences x 32 query heads per layer."""
+    from paper_2407_15891_amd.workloads import retrieval_pairs_stack
+    table = retrieval_pairs_stack(32, 8, 0.15, 5000)
+    assert table.sum() == 38
+    counts = table.sum(1)
+    layers = [int(np.flatnonzero(counts == c)[0]) for c in sorted(set(counts.tolist()))]
+    say(f"full size: config 5, sampled layers {layers} (retrieval KV heads per layer: {[int(counts[l]) for l in layers]})")
+    check_at = (0, 127, 255)
+    for layer in layers:
+        w = make_workload(5, DEV, layer=layer)
+        assert w.max_new == 256 and (w.mask == table[layer]).all()
+        cache = razor.RazorCache.from_workload(w)
+        cache.compress(w.K, w.V)
+        oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, w.n_sink, w.window, max_new=256)
+        w.K = w.V = None
+        say(f"    layer {layer}: compressed, oracle cache built")
+        np.testing.assert_array_equal(cache.desc()["n_dropped"], oc.N_d.reshape(-1))
+        comp = cache.comp.cpu().numpy().reshape(w.B, w.Hkv, 2, w.d).astype(np.float64)
+        np.testing.assert_allclose(comp[:, :, 0], oc.khat, rtol=0, atol=3e-5)
+        np.testing.assert_allclose(comp[:, :, 1], oc.vhat, rtol=0, atol=3e-5)
+        worst = (0.0, 0.0)
+        for t in range(256):
+            Q, k, v = w.step_inputs(t)
+            out = cache.decode(Q, k, v)
+            oc.append(k.cpu(), v.cpu())
+            if t in check_at:
+                e = check_output(out, oc.decode(Q.cpu(), w.scale), f"config 5 layer {layer} step {t}")
+                worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+        np.testing.assert_array_equal(cache.desc()["rows"], oc.rows().reshape(-1))
+        say(f"    layer {layer}: 256 steps, checked {check_at}: max-abs {worst[0]:.2e}, row-rel {worst[1]:.2e}")
+        del cache, oc
+        torch.cuda.empty_cache()
