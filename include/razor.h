@@ -52,6 +52,8 @@
 extern "C" {
 #endif
 
+#define RAZOR_API __attribute__((visibility("default")))
+
 typedef enum razor_dtype { RAZOR_F32 = 0, RAZOR_BF16 = 1 } razor_dtype;
 
 typedef enum razor_status {
@@ -116,7 +118,7 @@ typedef struct razor_sizes {
  * desc_host[batch * n_kv_heads] and kept_idx_host[total_rows] may each be NULL (sizes only;
  * kept positions ascending per head, heads in desc order).  sizes must not be NULL.
  */
-int razor_plan(const razor_params *p, const int32_t *seq_lens_host,
+RAZOR_API int razor_plan(const razor_params *p, const int32_t *seq_lens_host,
                const uint8_t *retrieval_mask_host, razor_head_desc *desc_host,
                int32_t *kept_idx_host, razor_sizes *sizes);
 
@@ -128,7 +130,7 @@ int razor_plan(const razor_params *p, const int32_t *seq_lens_host,
  * After the call the arena is self-contained: the caller may release K and V.
  * Means are accumulated in fp32 in a fixed order (bit-reproducible run to run).
  */
-int razor_compress(const razor_params *p, const void *K, const void *V,
+RAZOR_API int razor_compress(const razor_params *p, const void *K, const void *V,
                    int64_t stride_b, int64_t stride_h, int64_t stride_n,
                    const int32_t *seq_lens_host, const uint8_t *retrieval_mask_host,
                    void *arena, float *comp, razor_head_desc *desc_dev,
@@ -144,7 +146,7 @@ int razor_compress(const razor_params *p, const void *K, const void *V,
  * p must describe the same batch / heads / head_dim / dtype the cache was built with.
  * Results are bit-reproducible run to run (no floating-point atomics).
  */
-int razor_decode_attn(const razor_params *p, const void *Q, const void *k_new,
+RAZOR_API int razor_decode_attn(const razor_params *p, const void *Q, const void *k_new,
                       const void *v_new, void *arena, const float *comp,
                       razor_head_desc *desc_dev, void *O, void *workspace,
                       size_t workspace_bytes, void *stream);
@@ -156,11 +158,11 @@ int razor_decode_attn(const razor_params *p, const void *Q, const void *k_new,
  * alone.  Pass NULL, NULL to switch the hook off (the default).  The events stay owned
  * by the caller.  Always returns RAZOR_OK.
  */
-int razor_profile_events(void *ev_start, void *ev_stop);
+RAZOR_API int razor_profile_events(void *ev_start, void *ev_stop);
 
 /* Text for a razor_status; for RAZOR_EHIP the text of the last HIP error seen by the
  * calling thread.  The pointer stays valid until the thread's next failing call. */
-const char *razor_strerror(int status);
+RAZOR_API const char *razor_strerror(int status);
 
 #ifdef __cplusplus
 }
