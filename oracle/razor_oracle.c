@@ -8,6 +8,7 @@
  *
  *   oracle_select       Algorithm 1, steps 2-3: which cache rows a head keeps
  *   oracle_comp_token   Eq.(4): the compensation token (mean of dropped rows)
+ *   oracle_comp_token2  Eq.(4) over a dropped set that reaches into the appended rows
  *   oracle_attn_head    Eq.(5): attention over kept rows + compensation token
  *   oracle_decode_batch Algorithm 1, step 5: per-head dispatch over a batch
  *
@@ -92,6 +93,34 @@ void oracle_comp_token(const void *K_head, const void *V_head, int dtype,
 }
 
 /*
+ * Eq.(4) when the dropped set spans two stores: positions [d_lo, d_hi) of the prefill
+ * cache and rows [n_lo, n_hi) of the rows appended during decoding (sliding mode, where
+ * Algorithm 1 is re-applied to the whole sequence after every generated token).
+ */
+void oracle_comp_token2(const void *K_head, const void *V_head, int dtype, int64_t stride_n,
+                        int d, int64_t d_lo, int64_t d_hi,
+                        const void *K_new, const void *V_new, int64_t stride_new,
+                        int64_t n_lo, int64_t n_hi, double *khat, double *vhat)
+{
+    int64_t N_d = (d_hi - d_lo) + (n_hi - n_lo);
+    for (int c = 0; c < d; ++c) khat[c] = vhat[c] = 0.0;
+    for (int64_t m = d_lo; m < d_hi; ++m)
+        for (int c = 0; c < d; ++c) {
+            khat[c] += widen(K_head, dtype, m * stride_n + c);
+            vhat[c] += widen(V_head, dtype, m * stride_n + c);
+        }
+    for (int64_t m = n_lo; m < n_hi; ++m)
+        for (int c = 0; c < d; ++c) {
+            khat[c] += widen(K_new, dtype, m * stride_new + c);
+            vhat[c] += widen(V_new, dtype, m * stride_new + c);
+        }
+    for (int c = 0; c < d; ++c) {
+        khat[c] /= (double)N_d;
+        vhat[c] /= (double)N_d;
+    }
+}
+
+/*
  * Eq.(5) for one query vector q (length d):
  *
  *        N_d e^{q.khat} vhat + sum_{n kept} e^{q.k_n} v_n
@@ -160,7 +189,8 @@ void oracle_attn_head(const double *q, int d, double scale,
  *   K, V     prefill cache, element strides (stride_b, stride_h, stride_n)
  *   kept     concatenated kept positions, head (b,h) owns
  *            kept[kept_off[b*Hkv+h] .. kept_off[b*Hkv+h+1])
- *   K_new,V_new [B, n_kv_heads, cap_new, d] appended rows, n_new of them valid
+ *   K_new,V_new [B, n_kv_heads, cap_new, d] appended rows, n_new of them valid; head (b,h)
+ *            keeps rows [new_lo[b*Hkv+h], n_new) of them (new_lo == NULL: all)
  *   khat,vhat   [B, n_kv_heads, d] doubles;  N_d [B, n_kv_heads]
  *   out      [B, n_q_heads, d] doubles
  * Returns the number of threads used.
@@ -170,7 +200,7 @@ int oracle_decode_batch(const void *Q, const void *K, const void *V, int dtype,
                         int64_t stride_b, int64_t stride_h, int64_t stride_n,
                         const int64_t *kept, const int64_t *kept_off,
                         const void *K_new, const void *V_new, int64_t cap_new,
-                        int64_t n_new,
+                        int64_t n_new, const int64_t *new_lo,
                         const double *khat, const double *vhat,
                         const int64_t *N_d, double scale, double *out)
 {
@@ -190,10 +220,11 @@ int oracle_decode_batch(const void *Q, const void *K, const void *V, int dtype,
         for (int c = 0; c < d; ++c) qd[c] = widen(Q, dtype, (int64_t)bj * d + c);
         const char *Kh = (const char *)K + (b * stride_b + h * stride_h) * esz;
         const char *Vh = (const char *)V + (b * stride_b + h * stride_h) * esz;
-        const char *Kn = K_new ? (const char *)K_new + bh * cap_new * d * esz : NULL;
-        const char *Vn = V_new ? (const char *)V_new + bh * cap_new * d * esz : NULL;
+        int64_t lo_new = new_lo ? new_lo[bh] : 0;
+        const char *Kn = K_new ? (const char *)K_new + (bh * cap_new + lo_new) * d * esz : NULL;
+        const char *Vn = V_new ? (const char *)V_new + (bh * cap_new + lo_new) * d * esz : NULL;
         oracle_attn_head(qd, d, scale, Kh, Vh, dtype, stride_n,
-                         kept + kept_off[bh], n_kept, Kn, Vn, d, n_new,
+                         kept + kept_off[bh], n_kept, Kn, Vn, d, n_new - lo_new,
                          khat + bh * d, vhat + bh * d, N_d[bh], scratch,
                          out + (int64_t)bj * d);
         free(qd);

@@ -46,8 +46,10 @@ def lib():
         L.oracle_comp_token.restype = None
         L.oracle_comp_token.argtypes = [vp, vp, ci, i64, ci, i64, i64, vp, vp]
         L.oracle_decode_batch.restype = ci
+        L.oracle_comp_token2.restype = None
+        L.oracle_comp_token2.argtypes = [vp, vp, ci, i64, ci, i64, i64, vp, vp, i64, i64, i64, vp, vp]
         L.oracle_decode_batch.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, i64, i64, i64,
-                                          vp, vp, vp, vp, i64, i64, vp, vp, vp, dbl, vp]
+                                          vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, dbl, vp]
         L.oracle_compress_batch.restype = ci
         L.oracle_compress_batch.argtypes = [vp, vp, ci, ci, ci, ci, i64, i64, i64,
                                             vp, vp, i64, i64, vp, vp, vp, vp, vp]
@@ -93,9 +95,16 @@ class OracleCache:
     seq_lens[b] <= N is the valid length of sequence b; mask[h] != 0 marks a
     retrieval KV head.  Compression happens once, here (after prefill); decode
     steps append to every head and never evict.
+
+    sliding=True: Algorithm 1 is re-applied to the whole sequence (prefill + generated
+    tokens) after every generated token, so the window slides and the compensation token
+    of Eq.(4) absorbs every token that leaves it.  Stated literally: selection and the means
+    are recomputed from scratch at each decode.
     """
 
-    def __init__(self, K, V, seq_lens, mask, n_sink: int, window: int, max_new: int = 0):
+    def __init__(self, K, V, seq_lens, mask, n_sink: int, window: int, max_new: int = 0,
+                 sliding: bool = False):
+        self.sliding = bool(sliding)
         self.K, self.V = as_raw(K), as_raw(V)
         assert self.K.shape == self.V.shape and self.K.ndim == 4
         assert self.K.dtype == self.V.dtype
@@ -111,6 +120,9 @@ class OracleCache:
         assert self.seq_lens.shape == (B,) and self.mask.shape == (H,)
         assert (self.seq_lens >= 1).all() and (self.seq_lens <= N).all()
         self.n_sink, self.window = int(n_sink), int(window)
+        # sliding mode keeps the sinks inside the prefill (a shorter prefill would turn
+        # generated tokens into sinks; not supported by either side)
+        assert not self.sliding or (self.seq_lens >= self.n_sink).all()
 
         self.kept = np.empty(int(self.seq_lens.sum()) * H, dtype=np.int64)
         self.kept_off = np.zeros(B * H + 1, dtype=np.int64)
@@ -135,7 +147,60 @@ class OracleCache:
 
     def rows(self) -> np.ndarray:
         """Cached rows per (b, h), compensation entry not counted."""
+        if self.sliding:
+            return np.diff(self._reselect()[1]).reshape(self.B, self.H) + \
+                (self.n_new - self._reselect()[2]).reshape(self.B, self.H)
         return (np.diff(self.kept_off) + self.n_new).reshape(self.B, self.H)
+
+    def _reselect(self):
+        """Sliding mode: Algorithm 1 steps 2-3 on the sequence as it stands now (seq_len + n_new
+        tokens).  Returns kept prefill positions (concatenated), their offsets, the first kept
+        appended row per head, and the dropped ranges in both stores."""
+        B, H = self.B, self.H
+        kept, off = [], np.zeros(B * H + 1, np.int64)
+        new_lo = np.zeros(B * H, np.int64)
+        d_pre = np.zeros((B * H, 2), np.int64)
+        d_new = np.zeros((B * H, 2), np.int64)
+        for b in range(B):
+            N, T = int(self.seq_lens[b]), int(self.seq_lens[b]) + self.n_new
+            for h in range(H):
+                i = b * H + h
+                idx, lo, hi = select(T, bool(self.mask[h]), self.n_sink, self.window)
+                pre = idx[idx < N]
+                app = idx[idx >= N] - N
+                # kept appended rows are a suffix: everything older has moved into the dropped set
+                assert len(app) == 0 or (app == np.arange(app[0], self.n_new)).all()
+                new_lo[i] = app[0] if len(app) else self.n_new
+                kept.append(pre)
+                off[i + 1] = off[i] + len(pre)
+                d_pre[i] = (min(lo, N), min(hi, N))
+                d_new[i] = (max(lo, N) - N, max(hi, N) - N)
+        kept = np.concatenate(kept) if kept else np.zeros(0, np.int64)
+        return np.ascontiguousarray(kept, dtype=np.int64), off, new_lo, d_pre, d_new
+
+    def _recompute_tokens(self):
+        """Sliding mode: Eq.(4) from scratch over the dropped set as it stands now."""
+        kept, off, new_lo, d_pre, d_new = self._reselect()
+        B, H, d = self.B, self.H, self.d
+        es = self.K.itemsize
+        khat = np.zeros((B, H, d)); vhat = np.zeros((B, H, d)); N_d = np.zeros((B, H), np.int64)
+        for b in range(B):
+            for h in range(H):
+                i = b * H + h
+                n = int(d_pre[i, 1] - d_pre[i, 0] + d_new[i, 1] - d_new[i, 0])
+                N_d[b, h] = n
+                if n == 0:
+                    continue
+                kh, vh = np.zeros(d), np.zeros(d)
+                lib().oracle_comp_token2(
+                    self.K.ctypes.data + (b * self.strides[0] + h * self.strides[1]) * es,
+                    self.V.ctypes.data + (b * self.strides[0] + h * self.strides[1]) * es,
+                    self.dtype, self.strides[2], d, int(d_pre[i, 0]), int(d_pre[i, 1]),
+                    self.K_new.ctypes.data + i * self.cap_new * d * es,
+                    self.V_new.ctypes.data + i * self.cap_new * d * es, d,
+                    int(d_new[i, 0]), int(d_new[i, 1]), _ptr(kh), _ptr(vh))
+                khat[b, h], vhat[b, h] = kh, vh
+        return kept, off, new_lo, khat, vhat, N_d
 
     def append(self, k_new, v_new) -> None:
         k_new, v_new = as_raw(k_new), as_raw(v_new)
@@ -151,10 +216,15 @@ class OracleCache:
         B, Hq, d = Q.shape
         assert B == self.B and d == self.d and Hq % self.H == 0 and Q.dtype == self.K.dtype
         out = np.empty((B, Hq, d), dtype=np.float64)
+        if self.sliding:
+            self.kept, self.kept_off, new_lo, self.khat, self.vhat, self.N_d = self._recompute_tokens()
+        else:
+            new_lo = None
         N_d = self.N_d if use_comp else np.zeros_like(self.N_d)
         self.threads = lib().oracle_decode_batch(
             _ptr(Q), _ptr(self.K), _ptr(self.V), self.dtype, B, Hq, self.H, d, *self.strides,
             _ptr(self.kept), _ptr(self.kept_off), _ptr(self.K_new), _ptr(self.V_new),
-            self.cap_new, self.n_new, _ptr(self.khat), _ptr(self.vhat),
-            _ptr(np.ascontiguousarray(N_d)), float(scale), _ptr(out))
+            self.cap_new, self.n_new, _ptr(new_lo), _ptr(np.ascontiguousarray(self.khat)),
+            _ptr(np.ascontiguousarray(self.vhat)), _ptr(np.ascontiguousarray(N_d)), float(scale),
+            _ptr(out))
         return out
