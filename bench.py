@@ -33,7 +33,7 @@ def algorithmic_bytes_decode(desc, p_d, esize, B, Hq, use_comp=True):
     rows = int(desc["rows"].astype("int64").sum())
     n_comp = int((desc["n_dropped"] > 0).sum()) if use_comp else 0
     return rows * 2 * p_d * esize + n_comp * 2 * p_d * 4 + B * Hq * p_d * esize + B * Hq * p_d * 4 \
-        + desc.size * 32
+        + desc.size * desc.itemsize
 
 
 def measured_traffic(config):

@@ -86,18 +86,28 @@ typedef struct razor_params {
     float scale;         /* multiplies every logit, the compensation logit included; 1.0f is
                             Eq.(5) as printed, 1/sqrt(head_dim) what the evaluated models use */
     int32_t n_workers;   /* wavefronts to split a decode over; 0 = pick from the device */
+    int32_t sliding;     /* 0: compress once, decode appends and never evicts.
+                            1: Algorithm 1 re-applied after every generated token: once a
+                            non-retrieval head holds n_sink + window rows, an append overwrites its
+                            oldest window row, and that row first moves into the compensation token
+                            (khat += (k - khat) / (N_d + 1), likewise vhat, N_d += 1: Eq.(4) over the
+                            enlarged dropped set).  Needs window >= 1 and every seq_len >= n_sink. */
 } razor_params;
 
 /* One entry per (sequence b, KV head h).  Written by razor_plan (host copy) and
- * razor_compress (device copy); `rows` and the overflow flag of the device copy
- * are updated by razor_decode_attn when it appends. */
+ * razor_compress (device copy); `rows`, `n_dropped`, `evicted` and flags of the device
+ * copy are updated by razor_decode_attn when it appends. */
 typedef struct razor_head_desc {
     int64_t row_off;   /* first row of this head's region, in rows of 2*head_dim elements */
     int64_t kept_off;  /* first entry of this head in kept_idx                             */
     int32_t rows;      /* cached rows (compensation token not counted)                     */
-    int32_t cap;       /* rows reserved; multiple of 16, >= rows at plan time + max_new   */
+    int32_t cap;       /* rows reserved; multiple of 16, >= rows at plan time + max_new
+                          (sliding, non-retrieval: >= min(that, n_sink + window))          */
     int32_t n_dropped; /* N_d of Eq.(4)/(5); 0 when nothing was dropped                    */
     uint32_t flags;    /* RAZOR_HEAD_*                                                     */
+    int32_t evicted;   /* sliding mode: rows overwritten so far; the next one is row
+                          n_sink + evicted % window                                        */
+    int32_t reserved;
 } razor_head_desc;
 
 typedef struct razor_sizes {
@@ -140,14 +150,16 @@ RAZOR_API int razor_compress(const razor_params *p, const void *K, const void *V
 /*
  * One decode step.  If k_new and v_new ([batch, n_kv_heads, head_dim]) are non-NULL the
  * new token is first appended to every head (rows += 1; a full head sets
- * RAZOR_HEAD_OVERFLOW and skips the append), then Q [batch, n_q_heads, head_dim] attends:
+ * RAZOR_HEAD_OVERFLOW and skips the append; in sliding mode a non-retrieval head that holds
+ * n_sink + window rows instead moves its oldest window row into comp and overwrites it),
+ * then Q [batch, n_q_heads, head_dim] attends:
  * retrieval heads by plain softmax attention, the others by Eq.(5), logits scaled by
  * p->scale, accumulation in fp32.  O [batch, n_q_heads, head_dim] in p->out_dtype.
  * p must describe the same batch / heads / head_dim / dtype the cache was built with.
  * Results are bit-reproducible run to run (no floating-point atomics).
  */
 RAZOR_API int razor_decode_attn(const razor_params *p, const void *Q, const void *k_new,
-                      const void *v_new, void *arena, const float *comp,
+                      const void *v_new, void *arena, float *comp,
                       razor_head_desc *desc_dev, void *O, void *workspace,
                       size_t workspace_bytes, void *stream);
 

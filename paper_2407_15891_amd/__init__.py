@@ -37,13 +37,15 @@ class RazorParams(ctypes.Structure):
                 ("n_sink", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("max_new", ctypes.c_int32), ("use_comp", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
-                ("scale", ctypes.c_float), ("n_workers", ctypes.c_int32)]
+                ("scale", ctypes.c_float), ("n_workers", ctypes.c_int32),
+                ("sliding", ctypes.c_int32)]
 
 
 class RazorHeadDesc(ctypes.Structure):
     _fields_ = [("row_off", ctypes.c_int64), ("kept_off", ctypes.c_int64),
                 ("rows", ctypes.c_int32), ("cap", ctypes.c_int32),
-                ("n_dropped", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("n_dropped", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("evicted", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class RazorSizes(ctypes.Structure):
@@ -54,8 +56,8 @@ class RazorSizes(ctypes.Structure):
 
 
 DESC_DTYPE = np.dtype([("row_off", "<i8"), ("kept_off", "<i8"), ("rows", "<i4"), ("cap", "<i4"),
-                       ("n_dropped", "<i4"), ("flags", "<u4")])
-assert DESC_DTYPE.itemsize == ctypes.sizeof(RazorHeadDesc) == 32
+                       ("n_dropped", "<i4"), ("flags", "<u4"), ("evicted", "<i4"), ("reserved", "<i4")])
+assert DESC_DTYPE.itemsize == ctypes.sizeof(RazorHeadDesc) == 40
 
 
 class RazorError(RuntimeError):
@@ -152,7 +154,8 @@ class RazorCache:
     def __init__(self, *, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
                  seq_lens, retrieval_mask, n_sink: int, window: int, max_new: int,
                  dtype, scale: Optional[float] = None, out_dtype=None, use_comp: bool = True,
-                 n_workers: int = 0, device="cuda", want_kept_idx: bool = False):
+                 n_workers: int = 0, device="cuda", want_kept_idx: bool = False,
+                 sliding: bool = False):
         import torch
         self.torch = torch
         code = {torch.float32: RAZOR_F32, torch.bfloat16: RAZOR_BF16}
@@ -160,7 +163,8 @@ class RazorCache:
         self.out_dtype = out_dtype or torch.float32
         self.params = RazorParams(batch, n_q_heads, n_kv_heads, head_dim, n_sink, window, max_new,
                                   int(use_comp), code[dtype], code[self.out_dtype],
-                                  float(scale if scale is not None else head_dim ** -0.5), n_workers)
+                                  float(scale if scale is not None else head_dim ** -0.5), n_workers,
+                                  int(sliding))
         self.seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
         self.mask = np.ascontiguousarray(retrieval_mask, dtype=np.uint8)
         assert self.seq_lens.shape == (batch,) and self.mask.shape == (n_kv_heads,)

@@ -37,13 +37,6 @@ constexpr float kNegInf = -__builtin_huge_valf();
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Rows a head holds during this step: the stored count plus the token being appended
-// (an append to a full head is skipped everywhere by the same test).
-__device__ __forceinline__ int rows_this_step(const razor_head_desc &e, int has_new)
-{
-    return e.rows + ((has_new && e.rows < e.cap) ? 1 : 0);
-}
-
 // Debug builds (-DRAZOR_TIMELINE) stamp the 100 MHz wall clock at a few points of every
 // streaming wave and drop the stamps behind the last partial slot; off in the product.
 #ifdef RAZOR_TIMELINE
@@ -81,6 +74,46 @@ __device__ __forceinline__ void append_row(const razor_head_desc &e, int head, c
     __threadfence();   // the loads of this wave that follow must see the row
 }
 
+// Sliding mode, head full: row `slot` (the oldest window row) first moves into the
+// compensation token -- khat += (k - khat) / (N_d + 1), likewise vhat: Eq.(4) over the
+// dropped set enlarged by that row -- and is then overwritten by the new token.  Lanes
+// 0..LPR-1 handle the K pieces, lanes 32..32+LPR-1 the V pieces.  Called by the one wave whose
+// range holds the row's block; comp is not read by anyone else before the combine kernel.
+template <int RB, int DTYPE>
+__device__ __forceinline__ void evict_row(const razor_head_desc &e, int head, int slot, char *kplane,
+                                          char *vplane, const char *__restrict__ k_new,
+                                          const char *__restrict__ v_new, float *__restrict__ comp,
+                                          int lane)
+{
+    constexpr int LPR = RB / 16;
+    constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
+    constexpr int NE = 16 / ES, D = RB / ES;
+    const int which = lane >> 5, piece = lane & 31;
+    if (piece < LPR) {
+        char *pos = which ? vplane + (int64_t)slot * RB + piece * 16
+                          : kplane + (int64_t)(slot / kBlockRows) * kBlockRows * RB +
+                                (piece * 16 + slot % kBlockRows) * 16;
+        const uint4 old = *reinterpret_cast<const uint4 *>(pos);
+        float x[NE];
+        if constexpr (DTYPE == RAZOR_F32) {
+            x[0] = __uint_as_float(old.x); x[1] = __uint_as_float(old.y);
+            x[2] = __uint_as_float(old.z); x[3] = __uint_as_float(old.w);
+        } else {
+            x[0] = __uint_as_float(old.x << 16); x[1] = __uint_as_float(old.x & 0xffff0000u);
+            x[2] = __uint_as_float(old.y << 16); x[3] = __uint_as_float(old.y & 0xffff0000u);
+            x[4] = __uint_as_float(old.z << 16); x[5] = __uint_as_float(old.z & 0xffff0000u);
+            x[6] = __uint_as_float(old.w << 16); x[7] = __uint_as_float(old.w & 0xffff0000u);
+        }
+        float *c = comp + ((size_t)head * 2 + which) * D + piece * NE;
+        const float inv = 1.f / (float)(e.n_dropped + 1);
+#pragma unroll
+        for (int k = 0; k < NE; ++k) c[k] += (x[k] - c[k]) * inv;
+        *reinterpret_cast<uint4 *>(pos) =
+            *reinterpret_cast<const uint4 *>((which ? v_new : k_new) + (int64_t)head * RB + piece * 16);
+    }
+    __threadfence();   // the loads of this wave that follow must see the new row
+}
+
 // ---------------------------------------------------------------- partial, bf16 / matrix cores
 //
 // Lane l = 16 * kg + n.  For one 16-row block:
@@ -99,8 +132,9 @@ template <int D, int PF>
 __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
     const uint16_t *__restrict__ Q, char *__restrict__ arena,
     const razor_head_desc *__restrict__ desc, const char *__restrict__ k_new,
-    const char *__restrict__ v_new, int32_t *__restrict__ prefix, float *__restrict__ part_ml,
-    float *__restrict__ part_acc, int n_heads, int n_kv_heads, int g, int n_workers,
+    const char *__restrict__ v_new, float *__restrict__ comp, int32_t *__restrict__ prefix,
+    int32_t *__restrict__ nd_step, float *__restrict__ part_ml, float *__restrict__ part_acc,
+    int n_heads, int n_kv_heads, int g, int n_workers, int sliding, int n_sink, int window,
     float scale_log2e)
 {
     constexpr int RB = D * 2;     // bytes per row
@@ -116,10 +150,13 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
     long long stamp_segments = 0;
 #endif
     RAZOR_STAMP(0);
-    const CachedBlocks count{has_new};
+    const CachedBlocks count{has_new, sliding, n_sink, window};
     const int total = total_blocks(count, desc, n_heads, lane);
     const int per = blocks_per_worker(total, n_workers);
-    if (w == 0) write_prefix(count, desc, n_heads, lane, per, prefix);
+    if (w == 0) {   // what the combine kernel needs, taken before anything is committed
+        write_prefix(count, desc, n_heads, lane, per, prefix);
+        for (int idx = lane; idx < n_heads; idx += 64) nd_step[idx] = count.step_n_dropped(desc, idx);
+    }
     int lo = w * per;
     const int hi = lo + per < total ? lo + per : total;
     if (lo >= hi) return;
@@ -129,19 +166,25 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
 
     while (lo < hi) {
         razor_head_desc e = desc[i];
-        int rows = rows_this_step(e, has_new);
+        int rows = count.rows_of(e.rows, e.cap, e.flags);
         while (first + (rows + kBlockRows - 1) / kBlockRows <= lo) {   // heads without a block here
             first += (rows + kBlockRows - 1) / kBlockRows;
             e = desc[++i];
-            rows = rows_this_step(e, has_new);
+            rows = count.rows_of(e.rows, e.cap, e.flags);
         }
         const int head_end = first + (rows + kBlockRows - 1) / kBlockRows;
         const int seg_end = hi < head_end ? hi : head_end;
         const int b = i / n_kv_heads, h = i % n_kv_heads;
         char *kplane = arena + e.row_off * 2 * RB;
         char *vplane = kplane + (int64_t)e.cap * RB;
-        if (rows > e.rows && e.rows / kBlockRows >= lo - first && e.rows / kBlockRows < seg_end - first)
-            append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
+        if (has_new) {   // the wave that owns the block of the row the new token goes to stores it
+            const bool slides = count.slides(e.rows, e.flags);
+            const int slot = slides ? n_sink + e.evicted % window : e.rows;
+            if ((slides || rows > e.rows) && slot / kBlockRows >= lo - first && slot / kBlockRows < seg_end - first) {
+                if (slides) evict_row<RB, RAZOR_BF16>(e, i, slot, kplane, vplane, k_new, v_new, comp, lane);
+                else append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
+            }
+        }
 
         bf16x8 qreg[NS];
 #pragma unroll
@@ -267,8 +310,9 @@ template <int D, int G, int PF>
 __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
     const float *__restrict__ Q, char *__restrict__ arena,
     const razor_head_desc *__restrict__ desc, const char *__restrict__ k_new,
-    const char *__restrict__ v_new, int32_t *__restrict__ prefix, float *__restrict__ part_ml,
-    float *__restrict__ part_acc, int n_heads, int n_kv_heads, int g, int n_workers,
+    const char *__restrict__ v_new, float *__restrict__ comp, int32_t *__restrict__ prefix,
+    int32_t *__restrict__ nd_step, float *__restrict__ part_ml, float *__restrict__ part_acc,
+    int n_heads, int n_kv_heads, int g, int n_workers, int sliding, int n_sink, int window,
     float scale_log2e)
 {
     constexpr int RB = D * 4;
@@ -287,10 +331,13 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
     long long stamp_segments = 0;
 #endif
     RAZOR_STAMP(0);
-    const CachedBlocks count{has_new};
+    const CachedBlocks count{has_new, sliding, n_sink, window};
     const int total = total_blocks(count, desc, n_heads, lane);
     const int per = blocks_per_worker(total, n_workers);
-    if (w == 0) write_prefix(count, desc, n_heads, lane, per, prefix);
+    if (w == 0) {   // what the combine kernel needs, taken before anything is committed
+        write_prefix(count, desc, n_heads, lane, per, prefix);
+        for (int idx = lane; idx < n_heads; idx += 64) nd_step[idx] = count.step_n_dropped(desc, idx);
+    }
     int lo = w * per;
     const int hi = lo + per < total ? lo + per : total;
     if (lo >= hi) return;
@@ -300,19 +347,25 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
 
     while (lo < hi) {
         razor_head_desc e = desc[i];
-        int rows = rows_this_step(e, has_new);
+        int rows = count.rows_of(e.rows, e.cap, e.flags);
         while (first + (rows + kBlockRows - 1) / kBlockRows <= lo) {   // heads without a block here
             first += (rows + kBlockRows - 1) / kBlockRows;
             e = desc[++i];
-            rows = rows_this_step(e, has_new);
+            rows = count.rows_of(e.rows, e.cap, e.flags);
         }
         const int head_end = first + (rows + kBlockRows - 1) / kBlockRows;
         const int seg_end = hi < head_end ? hi : head_end;
         const int b = i / n_kv_heads, h = i % n_kv_heads;
         char *kplane = arena + e.row_off * 2 * RB;
         char *vplane = kplane + (int64_t)e.cap * RB;
-        if (rows > e.rows && e.rows / kBlockRows >= lo - first && e.rows / kBlockRows < seg_end - first)
-            append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
+        if (has_new) {   // the wave that owns the block of the row the new token goes to stores it
+            const bool slides = count.slides(e.rows, e.flags);
+            const int slot = slides ? n_sink + e.evicted % window : e.rows;
+            if ((slides || rows > e.rows) && slot / kBlockRows >= lo - first && slot / kBlockRows < seg_end - first) {
+                if (slides) evict_row<RB, RAZOR_F32>(e, i, slot, kplane, vplane, k_new, v_new, comp, lane);
+                else append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
+            }
+        }
 
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -440,8 +493,10 @@ template <int D>
 __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
     const void *__restrict__ Q, int q_dtype, const float *__restrict__ comp,
     razor_head_desc *__restrict__ desc, const int32_t *__restrict__ prefix,
-    const float *__restrict__ part_ml, const float *__restrict__ part_acc, void *__restrict__ O,
-    int out_dtype, int n_heads, int n_kv_heads, int g, int has_new, int use_comp, float scale_log2e)
+    const int32_t *__restrict__ nd_step, const float *__restrict__ part_ml,
+    const float *__restrict__ part_acc, void *__restrict__ O, int out_dtype, int n_heads,
+    int n_kv_heads, int g, int has_new, int use_comp, int sliding, int n_sink, int window,
+    float scale_log2e)
 {
     constexpr int C4 = D / 4;                    // float4 columns
     constexpr int GR = kCombineThreads / C4;     // slot groups working in parallel
@@ -454,7 +509,8 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
     const int bj = blockIdx.x, b = bj / n_q_heads, j = bj % n_q_heads;
     const int h = j / g, n = j % g, i = b * n_kv_heads + h;
     const razor_head_desc e = desc[i];
-    const bool has_comp = use_comp && e.n_dropped > 0;
+    const int n_dropped = nd_step[i];   // N_d of this step (a row evicted this step included)
+    const bool has_comp = use_comp && n_dropped > 0;
 
     if (wave == 0) {   // q . khat
         float part = 0.f;
@@ -469,7 +525,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
     const int first = prefix[i], last = prefix[i + 1], per = prefix[n_heads + 1];
     const int w0 = first / per;
     const int n_slots = last > first ? (last - 1) / per - w0 + 1 : 0;
-    const float m_comp = has_comp ? s_red[0] * scale_log2e + log2f((float)e.n_dropped) : kNegInf;
+    const float m_comp = has_comp ? s_red[0] * scale_log2e + log2f((float)n_dropped) : kNegInf;
     __syncthreads();
 
     float mx = m_comp;
@@ -524,11 +580,19 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
             *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(O) + (int64_t)bj * D + 4 * col) = pk;
         }
     }
-    // The step is over for this head: make the appended row permanent.  No other workgroup
-    // of this kernel reads rows or flags (block positions come from `prefix`).
+    // The step is over for this head: make the append permanent.  No other workgroup of this
+    // kernel reads what changes here (block positions come from `prefix`, N_d from `nd_step`).
     if (has_new && n == 0 && tid == 0) {
-        if (e.rows < e.cap) desc[i].rows = e.rows + 1;
-        else desc[i].flags = e.flags | RAZOR_HEAD_OVERFLOW;
+        const CachedBlocks count{has_new, sliding, n_sink, window};
+        if (count.slides(e.rows, e.flags)) {
+            desc[i].n_dropped = e.n_dropped + 1;
+            desc[i].evicted = e.evicted + 1;
+            desc[i].flags = e.flags | RAZOR_HEAD_COMP;
+        } else if (e.rows < e.cap) {
+            desc[i].rows = e.rows + 1;
+        } else {
+            desc[i].flags = e.flags | RAZOR_HEAD_OVERFLOW;
+        }
     }
 }
 
@@ -542,22 +606,25 @@ thread_local hipEvent_t g_profile_start = nullptr, g_profile_stop = nullptr;
 
 template <int G>
 void launch_partial_f32(int D, dim3 grid, hipStream_t s, const float *Q, char *arena,
-                        const razor_head_desc *desc, const char *kn, const char *vn, int32_t *prefix,
-                        float *ml, float *acc, int n_heads, int n_kv, int g, int workers, float sl2e)
+                        const razor_head_desc *desc, const char *kn, const char *vn, float *comp,
+                        int32_t *prefix, int32_t *nd, float *ml, float *acc, int n_heads, int n_kv,
+                        int g, int workers, int sliding, int n_sink, int window, float sl2e)
 {
     if (D == 64)
         hipLaunchKernelGGL((decode_partial_f32_kernel<64, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
-                           kn, vn, prefix, ml, acc, n_heads, n_kv, g, workers, sl2e);
+                           kn, vn, comp, prefix, nd, ml, acc, n_heads, n_kv, g, workers, sliding, n_sink,
+                           window, sl2e);
     else
         hipLaunchKernelGGL((decode_partial_f32_kernel<128, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
-                           kn, vn, prefix, ml, acc, n_heads, n_kv, g, workers, sl2e);
+                           kn, vn, comp, prefix, nd, ml, acc, n_heads, n_kv, g, workers, sliding, n_sink,
+                           window, sl2e);
 }
 
 }  // namespace
 }  // namespace razor
 
 extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const void *k_new,
-                                 const void *v_new, void *arena, const float *comp,
+                                 const void *v_new, void *arena, float *comp,
                                  razor_head_desc *desc_dev, void *O, void *workspace,
                                  size_t workspace_bytes, void *stream)
 {
@@ -583,6 +650,7 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
     const int D = p->head_dim, has_new = k_new != nullptr;
     char *wsb = static_cast<char *>(workspace);
     int32_t *prefix = reinterpret_cast<int32_t *>(wsb + ws.prefix_off);
+    int32_t *nd = reinterpret_cast<int32_t *>(wsb + ws.nd_off);
     float *ml = reinterpret_cast<float *>(wsb + ws.ml_off);
     float *acc = reinterpret_cast<float *>(wsb + ws.acc_off);
     char *a = static_cast<char *>(arena);
@@ -595,13 +663,15 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
         const uint16_t *q = static_cast<const uint16_t *>(Q);
         if (D == 128)
             hipLaunchKernelGGL((decode_partial_bf16_kernel<128, 2>), grid, dim3(256), 0, s, q, a, desc_dev,
-                               kn, vn, prefix, ml, acc, n_heads, p->n_kv_heads, g, workers, sl2e);
+                               kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers,
+                               p->sliding, p->n_sink, p->window, sl2e);
         else
             hipLaunchKernelGGL((decode_partial_bf16_kernel<64, 2>), grid, dim3(256), 0, s, q, a, desc_dev,
-                               kn, vn, prefix, ml, acc, n_heads, p->n_kv_heads, g, workers, sl2e);
+                               kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers,
+                               p->sliding, p->n_sink, p->window, sl2e);
     } else {
         const float *q = static_cast<const float *>(Q);
-#define RAZOR_F32_ARGS D, grid, s, q, a, desc_dev, kn, vn, prefix, ml, acc, n_heads, p->n_kv_heads, g, workers, sl2e
+#define RAZOR_F32_ARGS D, grid, s, q, a, desc_dev, kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers, p->sliding, p->n_sink, p->window, sl2e
         if (g == 1) launch_partial_f32<1>(RAZOR_F32_ARGS);
         else if (g == 2) launch_partial_f32<2>(RAZOR_F32_ARGS);
         else if (g <= 4) launch_partial_f32<4>(RAZOR_F32_ARGS);
@@ -614,12 +684,12 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
     const dim3 cgrid(p->batch * p->n_q_heads);
     if (D == 128)
         hipLaunchKernelGGL((combine_kernel<128>), cgrid, dim3(kCombineThreads), 0, s, Q, p->dtype, comp,
-                           desc_dev, prefix, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
-                           p->use_comp, sl2e);
+                           desc_dev, prefix, nd, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
+                           p->use_comp, p->sliding, p->n_sink, p->window, sl2e);
     else
         hipLaunchKernelGGL((combine_kernel<64>), cgrid, dim3(kCombineThreads), 0, s, Q, p->dtype, comp,
-                           desc_dev, prefix, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
-                           p->use_comp, sl2e);
+                           desc_dev, prefix, nd, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
+                           p->use_comp, p->sliding, p->n_sink, p->window, sl2e);
     RAZOR_HIP_CHECK(hipGetLastError());
     return RAZOR_OK;
 }

@@ -40,12 +40,32 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
 
 // How many 16-row blocks a head contributes to the axis being streamed.
 struct CachedBlocks {   // rows held this decode step (the token being appended included)
-    int has_new;
+    int has_new;        // a token is appended this step
+    int sliding;        // params.sliding
+    int n_sink, window;
+
+    // In sliding mode a non-retrieval head that already holds n_sink + window rows keeps that
+    // count: the new token overwrites its oldest window row.
+    __device__ __forceinline__ bool slides(int rows, uint32_t flags) const
+    {
+        return has_new && sliding && !(flags & RAZOR_HEAD_RETRIEVAL) && rows >= n_sink + window;
+    }
+    __device__ __forceinline__ int rows_of(int rows, int cap, uint32_t flags) const
+    {
+        if (!has_new || slides(rows, flags)) return rows;
+        return rows < cap ? rows + 1 : rows;   // an append to a full head is skipped
+    }
     __device__ __forceinline__ int operator()(const razor_head_desc *__restrict__ desc, int idx) const
     {
-        const int2 rc = *reinterpret_cast<const int2 *>(reinterpret_cast<const char *>(desc + idx) + 16);
-        const int rows = rc.x + ((has_new && rc.x < rc.y) ? 1 : 0);   // {rows, cap}
-        return (rows + kBlockRows - 1) / kBlockRows;
+        // {rows, cap, n_dropped, flags}
+        const int4 f = *reinterpret_cast<const int4 *>(reinterpret_cast<const char *>(desc + idx) + 16);
+        return (rows_of(f.x, f.y, (uint32_t)f.w) + kBlockRows - 1) / kBlockRows;
+    }
+    // N_d as it counts for this step (the row a sliding head evicts already included)
+    __device__ __forceinline__ int step_n_dropped(const razor_head_desc *__restrict__ desc, int idx) const
+    {
+        const int4 f = *reinterpret_cast<const int4 *>(reinterpret_cast<const char *>(desc + idx) + 16);
+        return f.z + (slides(f.x, (uint32_t)f.w) ? 1 : 0);
     }
 };
 struct DroppedBlocks {  // rows Eq.(4) averages

@@ -20,6 +20,7 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // same buffer; both layouts start at offset 0.
 struct DecodeWorkspace {
     size_t prefix_off;  // int32[n_heads + 2]: block prefix sums, then blocks-per-worker
+    size_t nd_off;      // int32[n_heads]: N_d of every head as it counts for this step
     size_t ml_off;      // float[slots][g][2]: running max (log2 domain) and denominator
     size_t acc_off;     // float[slots][g][head_dim]: unnormalised output
     size_t bytes;

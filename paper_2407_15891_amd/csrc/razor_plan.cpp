@@ -32,6 +32,8 @@ int check_params(const razor_params *p)
     if (!(p->scale == p->scale) || p->scale <= 0.0f) return RAZOR_EINVAL;
     if (p->n_workers < 0 || p->n_workers > RAZOR_MAX_WORKERS) return RAZOR_EINVAL;
     if ((int64_t)p->batch * p->n_kv_heads > (1 << 20)) return RAZOR_EINVAL;
+    if (p->sliding != 0 && p->sliding != 1) return RAZOR_EINVAL;
+    if (p->sliding && p->window < 1) return RAZOR_EINVAL;
     return RAZOR_OK;
 }
 
@@ -43,7 +45,8 @@ DecodeWorkspace decode_workspace(const razor_params &p)
     // a (worker, head) segment owns slot worker + head, so slots <= workers + heads
     w.slots = (int)(RAZOR_MAX_WORKERS + n_heads);
     w.prefix_off = 0;
-    w.ml_off = round_up((n_heads + 2) * sizeof(int32_t), 256);
+    w.nd_off = round_up((n_heads + 2) * sizeof(int32_t), 256);
+    w.ml_off = w.nd_off + round_up(n_heads * sizeof(int32_t), 256);
     w.acc_off = w.ml_off + round_up((size_t)w.slots * g * 2 * sizeof(float), 256);
     w.bytes = w.acc_off + (size_t)w.slots * g * p.head_dim * sizeof(float);
     return w;
@@ -86,6 +89,7 @@ int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *ma
     for (int b = 0; b < p.batch; ++b) {
         const int64_t N = seq_lens[b];
         if (N < 1) return RAZOR_EINVAL;
+        if (p.sliding && N < p.n_sink) return RAZOR_EINVAL;   // the sinks must lie inside the prefill
         for (int h = 0; h < p.n_kv_heads; ++h) {
             razor_head_desc &e = desc[(size_t)b * p.n_kv_heads + h];
             const bool retrieval = mask[h] != 0;
@@ -93,7 +97,10 @@ int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *ma
             // mean over an empty set in Eq.(4) is undefined, so the head keeps every row.
             const bool drops = !retrieval && N > (int64_t)p.n_sink + p.window;
             const int64_t rows = drops ? (int64_t)p.n_sink + p.window : N;
-            const int64_t cap = (int64_t)round_up((size_t)(rows + p.max_new), kBlockRows);
+            int64_t want = rows + p.max_new;
+            // a sliding head stops growing at n_sink + window rows
+            if (p.sliding && !retrieval && want > (int64_t)p.n_sink + p.window) want = (int64_t)p.n_sink + p.window;
+            const int64_t cap = (int64_t)round_up((size_t)want, kBlockRows);
             if (cap > INT32_MAX) return RAZOR_EINVAL;
             e.row_off = row_off;
             e.kept_off = kept_off;

@@ -317,3 +317,50 @@ def test_full_size_config5_sampled_layers():
         say(f"    layer {layer}: 256 steps, checked {check_at}: max-abs {worst[0]:.2e}, row-rel {worst[1]:.2e}")
         del cache, oc
         torch.cuda.empty_cache()
+
+
+# ----------------------------------------------------------------- sliding mode
+@pytest.mark.parametrize("cfg,context,window,batch,workers,steps", [
+    (1, 300, 40, 2, 0, 100),      # fp32; the 40-row ring wraps 2.5 times
+    (2, 700, 50, 1, 0, 120),      # bf16 MHA, outlier channels
+    (3, 900, 33, 2, 16, 80),      # GQA, few workers, window not a multiple of 16
+    (4, 400, 100, 5, 0, 60),      # ragged: some sequences start below n_sink + window and fill up first
+])
+def test_sliding_mode_parity(cfg, context, window, batch, workers, steps):
+    say(f"sliding parity cfg={cfg} context={context} window={window} batch={batch} workers={workers} steps={steps}")
+    w = make_workload(cfg, DEV, context=context, window=window, batch=batch, max_new=steps)
+    cache = razor.RazorCache.from_workload(w, n_workers=workers, sliding=True)
+    cache.compress(w.K, w.V)
+    oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, w.n_sink, w.window, max_new=steps, sliding=True)
+    worst = (0.0, 0.0)
+    for t in range(steps):
+        Q, k, v = w.step_inputs(t)
+        out = cache.decode(Q, k, v)
+        oc.append(k.cpu(), v.cpu())
+        e = check_output(out, oc.decode(Q.cpu(), w.scale), f"sliding step {t}")
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+        if t in (0, steps // 2, steps - 1):
+            d = cache.desc()
+            np.testing.assert_array_equal(d["rows"], oc.rows().reshape(-1))
+            np.testing.assert_array_equal(d["n_dropped"], oc.N_d.reshape(-1))
+            comp = cache.comp.cpu().numpy().reshape(w.B, w.Hkv, 2, w.d).astype(np.float64)
+            tol = 1e-5 * float(w.K.abs().max())
+            np.testing.assert_allclose(comp[:, :, 0], oc.khat, rtol=0, atol=tol)
+            np.testing.assert_allclose(comp[:, :, 1], oc.vhat, rtol=0, atol=tol)
+    d = cache.desc()
+    nonret = np.tile(w.mask == 0, w.B)
+    assert (d["rows"][nonret] <= w.n_sink + w.window).all() and not (d["flags"] & razor.RAZOR_HEAD_OVERFLOW).any()
+    say(f"    {steps} steps: max-abs {worst[0]:.2e}, row-rel {worst[1]:.2e}, evicted up to {int(d['evicted'].max())}")
+
+
+def test_sliding_mode_without_compensation_is_sinks_plus_window():
+    say("sliding, use_comp = 0: attention over the sinks and the last `window` tokens")
+    w = make_workload(3, DEV, context=500, window=64, batch=2, max_new=70)
+    cache = razor.RazorCache.from_workload(w, sliding=True, use_comp=False)
+    cache.compress(w.K, w.V)
+    oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, w.n_sink, w.window, max_new=70, sliding=True)
+    for t in range(70):
+        Q, k, v = w.step_inputs(t)
+        out = cache.decode(Q, k, v)
+        oc.append(k.cpu(), v.cpu())
+        check_output(out, oc.decode(Q.cpu(), w.scale, use_comp=False), f"sliding no-comp step {t}")

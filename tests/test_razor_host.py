@@ -16,7 +16,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def params(**kw):
     base = dict(batch=2, n_q_heads=8, n_kv_heads=4, head_dim=128, n_sink=4, window=32, max_new=8,
-                use_comp=1, dtype=razor.RAZOR_BF16, out_dtype=razor.RAZOR_F32, scale=0.088, n_workers=0)
+                use_comp=1, dtype=razor.RAZOR_BF16, out_dtype=razor.RAZOR_F32, scale=0.088, n_workers=0,
+                sliding=0)
     base.update(kw)
     return razor.RazorParams(**base)
 
@@ -44,7 +45,7 @@ def test_library_exports_every_declared_symbol():
     assert razor.razor_strerror(razor.RAZOR_OK) == "ok"
     assert "invalid" in razor.razor_strerror(razor.RAZOR_EINVAL)
     assert "workspace" in razor.razor_strerror(razor.RAZOR_ECAPACITY)
-    assert ctypes.sizeof(razor.RazorHeadDesc) == 32 and ctypes.sizeof(razor.RazorParams) == 48
+    assert ctypes.sizeof(razor.RazorHeadDesc) == 40 and ctypes.sizeof(razor.RazorParams) == 52
 
 
 @pytest.mark.parametrize("seq_lens,mask,n_sink,window", [
@@ -80,7 +81,7 @@ def test_plan_matches_oracle_table(seq_lens, mask, n_sink, window):
         off += e["cap"]
     assert sizes.total_cap == off
     assert sizes.arena_bytes == off * 2 * p.head_dim * 2
-    assert sizes.comp_bytes == B * H * 2 * p.head_dim * 4 and sizes.desc_bytes == B * H * 32
+    assert sizes.comp_bytes == B * H * 2 * p.head_dim * 4 and sizes.desc_bytes == B * H * 40
     assert sizes.kept_idx_bytes == 4 * total and sizes.workspace_bytes > 0
 
 
@@ -98,7 +99,7 @@ def test_plan_reproduces_table2_ratio():
     dict(head_dim=96), dict(head_dim=256), dict(n_q_heads=6), dict(n_q_heads=4 * 32), dict(batch=0),
     dict(n_sink=-1), dict(window=-1), dict(max_new=-1), dict(dtype=2), dict(out_dtype=7),
     dict(use_comp=2), dict(scale=0.0), dict(scale=float("nan")), dict(n_workers=-1),
-    dict(n_workers=razor.RAZOR_MAX_WORKERS + 1),
+    dict(n_workers=razor.RAZOR_MAX_WORKERS + 1), dict(sliding=2), dict(sliding=1, window=0),
 ])
 def test_bad_params_are_rejected(kw):
     p = params(**kw)
@@ -141,3 +142,17 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(razor, "LIB_PATH", "/nonexistent/librazor.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         razor.load_library()
+
+
+def test_plan_sliding_mode_caps_the_window_heads():
+    # sliding: a non-retrieval head never holds more than n_sink + window rows
+    p = params(batch=3, n_kv_heads=2, n_q_heads=2, n_sink=4, window=32, max_new=1000, sliding=1)
+    rc, desc, _, sizes = plan(p, [500, 20, 36], [0, 1], want_idx=False)
+    assert rc == razor.RAZOR_OK
+    rows = desc["rows"].reshape(3, 2).tolist()
+    cap = desc["cap"].reshape(3, 2).tolist()
+    assert rows == [[36, 500], [20, 20], [36, 36]]
+    assert cap == [[48, 1504], [48, 1024], [48, 1040]]          # 36 -> 48; retrieval: rows + 1000 rounded up
+    assert (desc["evicted"] == 0).all()
+    # the sinks must lie inside the prefill
+    assert plan(p, [500, 3, 36], [0, 1], want_idx=False)[0] == razor.RAZOR_EINVAL
