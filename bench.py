@@ -191,6 +191,8 @@ def main():
     ap.add_argument("--workers", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full", action="store_true", help="skip the uncompressed-cache comparison")
+    ap.add_argument("--sliding", action="store_true", help="decode in sliding mode (window heads evict "
+                    "their oldest row into the compensation token instead of growing)")
     ap.add_argument("--pmc-calib", action="store_true", help="also run one plain 1 GiB device copy, the "
                     "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
@@ -227,7 +229,7 @@ def main():
             c = razor.RazorCache(batch=w.B, n_q_heads=w.Hq, n_kv_heads=w.Hkv, head_dim=w.d,
                                  seq_lens=w.seq_lens, retrieval_mask=mask, n_sink=w.n_sink,
                                  window=w.window, max_new=max_new, dtype=w.dtype, scale=w.scale,
-                                 n_workers=args.workers, device=dev)
+                                 n_workers=args.workers, device=dev, sliding=args.sliding)
             c.compress(w.K, w.V)
             caches.append(c)
         torch.cuda.synchronize()
@@ -271,6 +273,9 @@ def main():
     # rows grow by one per visit; take the table at the middle of the timed region
     desc_avg = desc_mid.copy()
     desc_avg["rows"] = (desc0["rows"] + args.warmup // args.copies + args.steps // (2 * args.copies))
+    if args.sliding:   # window heads stay at n_sink + window rows
+        stay = (desc0["flags"] & razor.RAZOR_HEAD_RETRIEVAL) == 0
+        desc_avg["rows"][stay] = np.minimum(desc_avg["rows"][stay], w.n_sink + w.window)
     step_bytes = algorithmic_bytes_decode(desc_avg, w.d, esize, w.B, w.Hq)
     gbps = step_bytes / (wall / args.steps) / 1e9
     kernel_gbps = step_bytes / (kernel_ms * 1e-3) / 1e9
@@ -348,7 +353,7 @@ def main():
         "config": {"workload": f"BASELINE config {args.config}: {w.name}, batch {w.B}, {w.Hq} query / "
                                f"{w.Hkv} KV heads, head_dim {w.d}, context {w.N}, window {w.window}, "
                                f"{w.n_sink} sinks, {int(w.mask.sum())} retrieval KV heads; one step = "
-                               "append one token + compressed decode attention + combine",
+                               "append one token + compressed decode attention + combine" + (" (sliding mode)" if args.sliding else ""),
                    "cached_rows": kept_rows, "full_rows": full_rows, "copies_rotated": args.copies},
         "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
         "step_bytes": step_bytes,
