@@ -134,6 +134,11 @@ void oracle_comp_token2(const void *K_head, const void *V_head, int dtype, int64
  * compensation term (retrieval head, nothing dropped, or ablation).
  * The exponentials are shifted by the largest logit, which cancels in the
  * quotient.  scratch must hold n_kept + n_new doubles.
+ *
+ * ALiBi models (Eq.(1)): the logit of the key at position n for the query at position
+ * q_pos is scale * q.k_n - slope * (q_pos - n).  Prefill rows sit at their kept position,
+ * appended row a at new_pos0 + a.  slope = 0 gives the RoPE form (Eq.(3)).  The
+ * compensation token has no position; ALiBi callers pass N_d = 0.
  */
 void oracle_attn_head(const double *q, int d, double scale,
                       const void *K_head, const void *V_head, int dtype,
@@ -141,6 +146,7 @@ void oracle_attn_head(const double *q, int d, double scale,
                       const void *K_new, const void *V_new, int64_t stride_new,
                       int64_t n_new,
                       const double *khat, const double *vhat, int64_t N_d,
+                      double slope, int64_t q_pos, int64_t new_pos0,
                       double *scratch, double *out)
 {
     int64_t n_rows = n_kept + n_new;
@@ -153,6 +159,10 @@ void oracle_attn_head(const double *q, int d, double scale,
         double s = 0.0;
         for (int c = 0; c < d; ++c) s += q[c] * widen(kb, dtype, off + c);
         s *= scale;
+        if (slope != 0.0) {
+            int64_t pos = r < n_kept ? kept[r] : new_pos0 + (r - n_kept);
+            s -= slope * (double)(q_pos - pos);
+        }
         scratch[r] = s;
         if (s > M) M = s;
     }
@@ -192,6 +202,8 @@ void oracle_attn_head(const double *q, int d, double scale,
  *   K_new,V_new [B, n_kv_heads, cap_new, d] appended rows, n_new of them valid; head (b,h)
  *            keeps rows [new_lo[b*Hkv+h], n_new) of them (new_lo == NULL: all)
  *   khat,vhat   [B, n_kv_heads, d] doubles;  N_d [B, n_kv_heads]
+ *   slopes   ALiBi slope per query head (NULL: none); seq_lens[b] = prefill length, which
+ *            places appended row a at position seq_lens[b] + a and the query at the last one
  *   out      [B, n_q_heads, d] doubles
  * Returns the number of threads used.
  */
@@ -202,7 +214,8 @@ int oracle_decode_batch(const void *Q, const void *K, const void *V, int dtype,
                         const void *K_new, const void *V_new, int64_t cap_new,
                         int64_t n_new, const int64_t *new_lo,
                         const double *khat, const double *vhat,
-                        const int64_t *N_d, double scale, double *out)
+                        const int64_t *N_d, const double *slopes, const int64_t *seq_lens,
+                        double scale, double *out)
 {
     int g = n_q_heads / n_kv_heads;
     int n_threads = 1;
@@ -225,8 +238,9 @@ int oracle_decode_batch(const void *Q, const void *K, const void *V, int dtype,
         const char *Vn = V_new ? (const char *)V_new + (bh * cap_new + lo_new) * d * esz : NULL;
         oracle_attn_head(qd, d, scale, Kh, Vh, dtype, stride_n,
                          kept + kept_off[bh], n_kept, Kn, Vn, d, n_new - lo_new,
-                         khat + bh * d, vhat + bh * d, N_d[bh], scratch,
-                         out + (int64_t)bj * d);
+                         khat + bh * d, vhat + bh * d, N_d[bh],
+                         slopes ? slopes[j] : 0.0, seq_lens[b] + n_new - 1, seq_lens[b] + lo_new,
+                         scratch, out + (int64_t)bj * d);
         free(qd);
         free(scratch);
     }
@@ -243,7 +257,7 @@ int oracle_compress_batch(const void *K, const void *V, int dtype,
                           int B, int n_kv_heads, int d,
                           int64_t stride_b, int64_t stride_h, int64_t stride_n,
                           const int64_t *seq_lens, const uint8_t *mask,
-                          int64_t n_sink, int64_t window,
+                          int64_t n_sink, int64_t window, const int64_t *head_window,
                           int64_t *kept, int64_t *kept_off,
                           double *khat, double *vhat, int64_t *N_d)
 {
@@ -254,7 +268,9 @@ int oracle_compress_batch(const void *K, const void *V, int dtype,
     kept_off[0] = 0;
     for (int bh = 0; bh < B * n_kv_heads; ++bh) {
         int b = bh / n_kv_heads, h = bh % n_kv_heads;
-        int64_t n = oracle_select(seq_lens[b], mask[h] != 0, n_sink, window,
+        /* head_window: a buffer length per KV head (the vision scope L_h of Eq.(2)) */
+        int64_t n = oracle_select(seq_lens[b], mask[h] != 0, n_sink,
+                                  head_window ? head_window[h] : window,
                                   kept + kept_off[bh], &d_lo[bh], &d_hi[bh]);
         kept_off[bh + 1] = kept_off[bh] + n;
         N_d[bh] = d_hi[bh] - d_lo[bh];

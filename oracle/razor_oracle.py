@@ -49,10 +49,10 @@ def lib():
         L.oracle_comp_token2.restype = None
         L.oracle_comp_token2.argtypes = [vp, vp, ci, i64, ci, i64, i64, vp, vp, i64, i64, i64, vp, vp]
         L.oracle_decode_batch.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, i64, i64, i64,
-                                          vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, dbl, vp]
+                                          vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, dbl, vp]
         L.oracle_compress_batch.restype = ci
         L.oracle_compress_batch.argtypes = [vp, vp, ci, ci, ci, ci, i64, i64, i64,
-                                            vp, vp, i64, i64, vp, vp, vp, vp, vp]
+                                            vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -103,8 +103,13 @@ class OracleCache:
     """
 
     def __init__(self, K, V, seq_lens, mask, n_sink: int, window: int, max_new: int = 0,
-                 sliding: bool = False):
+                 sliding: bool = False, head_window=None, alibi_slopes=None):
+        """head_window: buffer length per KV head (overrides `window`); alibi_slopes: l_h of
+        Eq.(1) per query head -- the logits then carry -l_h (m - n) and decode must be called
+        with use_comp=False (the compensation token has no position)."""
         self.sliding = bool(sliding)
+        self.head_window = None if head_window is None else np.ascontiguousarray(head_window, dtype=np.int64)
+        self.slopes = None if alibi_slopes is None else np.ascontiguousarray(alibi_slopes, dtype=np.float64)
         self.K, self.V = as_raw(K), as_raw(V)
         assert self.K.shape == self.V.shape and self.K.ndim == 4
         assert self.K.dtype == self.V.dtype
@@ -131,7 +136,7 @@ class OracleCache:
         self.N_d = np.zeros((B, H), dtype=np.int64)
         self.threads = lib().oracle_compress_batch(
             _ptr(self.K), _ptr(self.V), self.dtype, B, H, d, *self.strides,
-            _ptr(self.seq_lens), _ptr(self.mask), self.n_sink, self.window,
+            _ptr(self.seq_lens), _ptr(self.mask), self.n_sink, self.window, _ptr(self.head_window),
             _ptr(self.kept), _ptr(self.kept_off), _ptr(self.khat), _ptr(self.vhat),
             _ptr(self.N_d))
         self.kept = self.kept[: self.kept_off[-1]].copy()
@@ -165,7 +170,8 @@ class OracleCache:
             N, T = int(self.seq_lens[b]), int(self.seq_lens[b]) + self.n_new
             for h in range(H):
                 i = b * H + h
-                idx, lo, hi = select(T, bool(self.mask[h]), self.n_sink, self.window)
+                win = self.window if self.head_window is None else int(self.head_window[h])
+                idx, lo, hi = select(T, bool(self.mask[h]), self.n_sink, win)
                 pre = idx[idx < N]
                 app = idx[idx >= N] - N
                 # kept appended rows are a suffix: everything older has moved into the dropped set
@@ -221,10 +227,11 @@ class OracleCache:
         else:
             new_lo = None
         N_d = self.N_d if use_comp else np.zeros_like(self.N_d)
+        assert self.slopes is None or (not use_comp and self.slopes.shape == (Hq,))
         self.threads = lib().oracle_decode_batch(
             _ptr(Q), _ptr(self.K), _ptr(self.V), self.dtype, B, Hq, self.H, d, *self.strides,
             _ptr(self.kept), _ptr(self.kept_off), _ptr(self.K_new), _ptr(self.V_new),
             self.cap_new, self.n_new, _ptr(new_lo), _ptr(np.ascontiguousarray(self.khat)),
-            _ptr(np.ascontiguousarray(self.vhat)), _ptr(np.ascontiguousarray(N_d)), float(scale),
-            _ptr(out))
+            _ptr(np.ascontiguousarray(self.vhat)), _ptr(np.ascontiguousarray(N_d)),
+            _ptr(self.slopes), _ptr(self.seq_lens), float(scale), _ptr(out))
         return out
