@@ -92,6 +92,14 @@ typedef struct razor_params {
                             oldest window row, and that row first moves into the compensation token
                             (khat += (k - khat) / (N_d + 1), likewise vhat, N_d += 1: Eq.(4) over the
                             enlarged dropped set).  Needs window >= 1 and every seq_len >= n_sink. */
+    int32_t reserved0;   /* must be 0 */
+    const int32_t *head_window_host; /* HOST, [n_kv_heads] or NULL: buffer length per KV head, used
+                            instead of `window` (ALiBi models: the vision scope L_h of Eq.(2),
+                            evaluated by the caller; a value >= the sequence keeps everything) */
+    const float *alibi_slopes;       /* DEVICE, [n_q_heads] or NULL.  Non-NULL selects Eq.(1): every
+                            logit becomes scale * q.k_n - slope[head] * (m - n), m the position of
+                            the query (the newest token), n of the key.  The compensation token has
+                            no position, so use_comp must be 0.  Only razor_decode_attn reads it. */
 } razor_params;
 
 /* One entry per (sequence b, KV head h).  Written by razor_plan (host copy) and
@@ -107,7 +115,7 @@ typedef struct razor_head_desc {
     uint32_t flags;    /* RAZOR_HEAD_*                                                     */
     int32_t evicted;   /* sliding mode: rows overwritten so far; the next one is row
                           n_sink + evicted % window                                        */
-    int32_t reserved;
+    int32_t window;    /* buffer length of this head (p->window or head_window_host[h])    */
 } razor_head_desc;
 
 typedef struct razor_sizes {
@@ -123,7 +131,8 @@ typedef struct razor_sizes {
 /*
  * Host-only; touches no GPU.  Algorithm 1 steps 2-3 for every (b, h):
  *   retrieval head, or seq_len <= n_sink + window:  keep rows [0, seq_len), N_d = 0;
- *   otherwise keep [0, n_sink) and [seq_len - window, seq_len), N_d = seq_len - n_sink - window.
+ *   otherwise keep [0, n_sink) and [seq_len - window, seq_len), N_d = seq_len - n_sink - window
+ *   (window = p->window, or p->head_window_host[h] when that table is given).
  * seq_lens_host[batch] (each >= 1), retrieval_mask_host[n_kv_heads] (non-zero = retrieval).
  * desc_host[batch * n_kv_heads] and kept_idx_host[total_rows] may each be NULL (sizes only;
  * kept positions ascending per head, heads in desc order).  sizes must not be NULL.

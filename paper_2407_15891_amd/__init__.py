@@ -38,14 +38,15 @@ class RazorParams(ctypes.Structure):
                 ("max_new", ctypes.c_int32), ("use_comp", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
                 ("scale", ctypes.c_float), ("n_workers", ctypes.c_int32),
-                ("sliding", ctypes.c_int32)]
+                ("sliding", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+                ("head_window_host", ctypes.c_void_p), ("alibi_slopes", ctypes.c_void_p)]
 
 
 class RazorHeadDesc(ctypes.Structure):
     _fields_ = [("row_off", ctypes.c_int64), ("kept_off", ctypes.c_int64),
                 ("rows", ctypes.c_int32), ("cap", ctypes.c_int32),
                 ("n_dropped", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("evicted", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("evicted", ctypes.c_int32), ("window", ctypes.c_int32)]
 
 
 class RazorSizes(ctypes.Structure):
@@ -56,7 +57,7 @@ class RazorSizes(ctypes.Structure):
 
 
 DESC_DTYPE = np.dtype([("row_off", "<i8"), ("kept_off", "<i8"), ("rows", "<i4"), ("cap", "<i4"),
-                       ("n_dropped", "<i4"), ("flags", "<u4"), ("evicted", "<i4"), ("reserved", "<i4")])
+                       ("n_dropped", "<i4"), ("flags", "<u4"), ("evicted", "<i4"), ("window", "<i4")])
 assert DESC_DTYPE.itemsize == ctypes.sizeof(RazorHeadDesc) == 40
 
 
@@ -155,7 +156,9 @@ class RazorCache:
                  seq_lens, retrieval_mask, n_sink: int, window: int, max_new: int,
                  dtype, scale: Optional[float] = None, out_dtype=None, use_comp: bool = True,
                  n_workers: int = 0, device="cuda", want_kept_idx: bool = False,
-                 sliding: bool = False):
+                 sliding: bool = False, head_window=None, alibi_slopes=None):
+        """head_window: buffer length per KV head (int array, overrides `window`);
+        alibi_slopes: float32 device tensor [n_q_heads] (selects Eq.(1) logits; use_comp must be False)."""
         import torch
         self.torch = torch
         code = {torch.float32: RAZOR_F32, torch.bfloat16: RAZOR_BF16}
@@ -164,7 +167,17 @@ class RazorCache:
         self.params = RazorParams(batch, n_q_heads, n_kv_heads, head_dim, n_sink, window, max_new,
                                   int(use_comp), code[dtype], code[self.out_dtype],
                                   float(scale if scale is not None else head_dim ** -0.5), n_workers,
-                                  int(sliding))
+                                  int(sliding), 0, None, None)
+        # the params struct points at these: keep them alive with the cache
+        self.head_window = None if head_window is None else np.ascontiguousarray(head_window, dtype=np.int32)
+        self.alibi_slopes = alibi_slopes
+        if self.head_window is not None:
+            assert self.head_window.shape == (n_kv_heads,)
+            self.params.head_window_host = self.head_window.ctypes.data
+        if alibi_slopes is not None:
+            assert alibi_slopes.dtype == torch.float32 and alibi_slopes.is_contiguous()
+            assert tuple(alibi_slopes.shape) == (n_q_heads,) and alibi_slopes.device.type == "cuda"
+            self.params.alibi_slopes = alibi_slopes.data_ptr()
         self.seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
         self.mask = np.ascontiguousarray(retrieval_mask, dtype=np.uint8)
         assert self.seq_lens.shape == (batch,) and self.mask.shape == (n_kv_heads,)

@@ -114,6 +114,30 @@ __device__ __forceinline__ void evict_row(const razor_head_desc &e, int head, in
     __threadfence();   // the loads of this wave that follow must see the new row
 }
 
+// ALiBi (Eq.(1)): how far behind the query (the newest token) cache row `row` lies.
+// Sinks keep their prefill position; window rows are in order until the head starts to
+// overwrite them (sliding mode), after which they form a ring whose newest row is known.
+struct RowDistance {
+    int n_sink, rows, total, newest, window;   // newest < 0: rows still in order
+    __device__ __forceinline__ RowDistance(const razor_head_desc &e, int rows_now, bool slides, int n_sink_)
+    {
+        const int evicted = e.evicted + (slides ? 1 : 0);
+        n_sink = n_sink_;
+        rows = rows_now;
+        total = rows_now + e.n_dropped + (slides ? 1 : 0);   // tokens seen so far
+        window = e.window;
+        newest = evicted > 0 ? n_sink_ + (evicted - 1) % e.window : -1;
+    }
+    __device__ __forceinline__ float operator()(int row) const
+    {
+        int dist;
+        if (row < n_sink) dist = total - 1 - row;
+        else if (newest >= 0) dist = newest - row + (newest < row ? window : 0);
+        else dist = rows - 1 - row;
+        return (float)dist;
+    }
+};
+
 // ---------------------------------------------------------------- partial, bf16 / matrix cores
 //
 // Lane l = 16 * kg + n.  For one 16-row block:
@@ -134,8 +158,8 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
     const razor_head_desc *__restrict__ desc, const char *__restrict__ k_new,
     const char *__restrict__ v_new, float *__restrict__ comp, int32_t *__restrict__ prefix,
     int32_t *__restrict__ nd_step, float *__restrict__ part_ml, float *__restrict__ part_acc,
-    int n_heads, int n_kv_heads, int g, int n_workers, int sliding, int n_sink, int window,
-    float scale_log2e)
+    int n_heads, int n_kv_heads, int g, int n_workers, int sliding, int n_sink,
+    const float *__restrict__ slopes, float scale_log2e)
 {
     constexpr int RB = D * 2;     // bytes per row
     constexpr int NS = D / 32;    // K loads (= first-product steps) per block
@@ -150,7 +174,7 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
     long long stamp_segments = 0;
 #endif
     RAZOR_STAMP(0);
-    const CachedBlocks count{has_new, sliding, n_sink, window};
+    const CachedBlocks count{has_new, sliding, n_sink};
     const int total = total_blocks(count, desc, n_heads, lane);
     const int per = blocks_per_worker(total, n_workers);
     if (w == 0) {   // what the combine kernel needs, taken before anything is committed
@@ -166,11 +190,11 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
 
     while (lo < hi) {
         razor_head_desc e = desc[i];
-        int rows = count.rows_of(e.rows, e.cap, e.flags);
+        int rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
         while (first + (rows + kBlockRows - 1) / kBlockRows <= lo) {   // heads without a block here
             first += (rows + kBlockRows - 1) / kBlockRows;
             e = desc[++i];
-            rows = count.rows_of(e.rows, e.cap, e.flags);
+            rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
         }
         const int head_end = first + (rows + kBlockRows - 1) / kBlockRows;
         const int seg_end = hi < head_end ? hi : head_end;
@@ -178,8 +202,8 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
         char *kplane = arena + e.row_off * 2 * RB;
         char *vplane = kplane + (int64_t)e.cap * RB;
         if (has_new) {   // the wave that owns the block of the row the new token goes to stores it
-            const bool slides = count.slides(e.rows, e.flags);
-            const int slot = slides ? n_sink + e.evicted % window : e.rows;
+            const bool slides = count.slides(e.rows, e.flags, e.window);
+            const int slot = slides ? n_sink + e.evicted % e.window : e.rows;
             if ((slides || rows > e.rows) && slot / kBlockRows >= lo - first && slot / kBlockRows < seg_end - first) {
                 if (slides) evict_row<RB, RAZOR_BF16>(e, i, slot, kplane, vplane, k_new, v_new, comp, lane);
                 else append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
@@ -195,6 +219,10 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
                     Q + ((int64_t)(b * n_kv_heads + h) * g + n) * D + (4 * s + kg) * 8);
             qreg[s] = __builtin_bit_cast(bf16x8, qv);
         }
+
+        const bool slides_now = count.slides(e.rows, e.flags, e.window);
+        const RowDistance distance(e, rows, slides_now, n_sink);
+        const float slope_l2e = (slopes && n < g) ? slopes[h * g + n] * 1.4426950408889634f : 0.f;
 
         float m = kNegInf, l = 0.f;
         f32x4 acc[VE];
@@ -225,6 +253,7 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 sv[r] = row0 + r < rows ? S[r] * scale_log2e : kNegInf;
+                if (slopes) sv[r] -= slope_l2e * distance(row0 + r);
                 bmax = fmaxf(bmax, sv[r]);
             }
             bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
@@ -312,8 +341,8 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
     const razor_head_desc *__restrict__ desc, const char *__restrict__ k_new,
     const char *__restrict__ v_new, float *__restrict__ comp, int32_t *__restrict__ prefix,
     int32_t *__restrict__ nd_step, float *__restrict__ part_ml, float *__restrict__ part_acc,
-    int n_heads, int n_kv_heads, int g, int n_workers, int sliding, int n_sink, int window,
-    float scale_log2e)
+    int n_heads, int n_kv_heads, int g, int n_workers, int sliding, int n_sink,
+    const float *__restrict__ slopes, float scale_log2e)
 {
     constexpr int RB = D * 4;
     constexpr int NS = RB / 64;     // K loads per block
@@ -331,7 +360,7 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
     long long stamp_segments = 0;
 #endif
     RAZOR_STAMP(0);
-    const CachedBlocks count{has_new, sliding, n_sink, window};
+    const CachedBlocks count{has_new, sliding, n_sink};
     const int total = total_blocks(count, desc, n_heads, lane);
     const int per = blocks_per_worker(total, n_workers);
     if (w == 0) {   // what the combine kernel needs, taken before anything is committed
@@ -347,11 +376,11 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
 
     while (lo < hi) {
         razor_head_desc e = desc[i];
-        int rows = count.rows_of(e.rows, e.cap, e.flags);
+        int rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
         while (first + (rows + kBlockRows - 1) / kBlockRows <= lo) {   // heads without a block here
             first += (rows + kBlockRows - 1) / kBlockRows;
             e = desc[++i];
-            rows = count.rows_of(e.rows, e.cap, e.flags);
+            rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
         }
         const int head_end = first + (rows + kBlockRows - 1) / kBlockRows;
         const int seg_end = hi < head_end ? hi : head_end;
@@ -359,8 +388,8 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
         char *kplane = arena + e.row_off * 2 * RB;
         char *vplane = kplane + (int64_t)e.cap * RB;
         if (has_new) {   // the wave that owns the block of the row the new token goes to stores it
-            const bool slides = count.slides(e.rows, e.flags);
-            const int slot = slides ? n_sink + e.evicted % window : e.rows;
+            const bool slides = count.slides(e.rows, e.flags, e.window);
+            const int slot = slides ? n_sink + e.evicted % e.window : e.rows;
             if ((slides || rows > e.rows) && slot / kBlockRows >= lo - first && slot / kBlockRows < seg_end - first) {
                 if (slides) evict_row<RB, RAZOR_F32>(e, i, slot, kplane, vplane, k_new, v_new, comp, lane);
                 else append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
@@ -374,6 +403,9 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        const bool slides_now = count.slides(e.rows, e.flags, e.window);
+        const RowDistance distance(e, rows, slides_now, n_sink);
 
         float m[G], l[G];
         float4 acc[G];
@@ -409,7 +441,8 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
                     }
                     dot += __shfl_xor(dot, 16);
                     dot += __shfl_xor(dot, 32);
-                    const float sv = valid ? dot * scale_log2e : kNegInf;
+                    float sv = valid ? dot * scale_log2e : kNegInf;
+                    if (slopes) sv -= slopes[h * g + j] * 1.4426950408889634f * distance(t * kBlockRows + n);
                     float bmax = sv;
                     bmax = fmaxf(bmax, __shfl_xor(bmax, 1));
                     bmax = fmaxf(bmax, __shfl_xor(bmax, 2));
@@ -495,8 +528,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
     razor_head_desc *__restrict__ desc, const int32_t *__restrict__ prefix,
     const int32_t *__restrict__ nd_step, const float *__restrict__ part_ml,
     const float *__restrict__ part_acc, void *__restrict__ O, int out_dtype, int n_heads,
-    int n_kv_heads, int g, int has_new, int use_comp, int sliding, int n_sink, int window,
-    float scale_log2e)
+    int n_kv_heads, int g, int has_new, int use_comp, int sliding, int n_sink, float scale_log2e)
 {
     constexpr int C4 = D / 4;                    // float4 columns
     constexpr int GR = kCombineThreads / C4;     // slot groups working in parallel
@@ -583,8 +615,8 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
     // The step is over for this head: make the append permanent.  No other workgroup of this
     // kernel reads what changes here (block positions come from `prefix`, N_d from `nd_step`).
     if (has_new && n == 0 && tid == 0) {
-        const CachedBlocks count{has_new, sliding, n_sink, window};
-        if (count.slides(e.rows, e.flags)) {
+        const CachedBlocks count{has_new, sliding, n_sink};
+        if (count.slides(e.rows, e.flags, e.window)) {
             desc[i].n_dropped = e.n_dropped + 1;
             desc[i].evicted = e.evicted + 1;
             desc[i].flags = e.flags | RAZOR_HEAD_COMP;
@@ -608,16 +640,16 @@ template <int G>
 void launch_partial_f32(int D, dim3 grid, hipStream_t s, const float *Q, char *arena,
                         const razor_head_desc *desc, const char *kn, const char *vn, float *comp,
                         int32_t *prefix, int32_t *nd, float *ml, float *acc, int n_heads, int n_kv,
-                        int g, int workers, int sliding, int n_sink, int window, float sl2e)
+                        int g, int workers, int sliding, int n_sink, const float *slopes, float sl2e)
 {
     if (D == 64)
         hipLaunchKernelGGL((decode_partial_f32_kernel<64, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
                            kn, vn, comp, prefix, nd, ml, acc, n_heads, n_kv, g, workers, sliding, n_sink,
-                           window, sl2e);
+                           slopes, sl2e);
     else
         hipLaunchKernelGGL((decode_partial_f32_kernel<128, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
                            kn, vn, comp, prefix, nd, ml, acc, n_heads, n_kv, g, workers, sliding, n_sink,
-                           window, sl2e);
+                           slopes, sl2e);
 }
 
 }  // namespace
@@ -664,14 +696,14 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
         if (D == 128)
             hipLaunchKernelGGL((decode_partial_bf16_kernel<128, 2>), grid, dim3(256), 0, s, q, a, desc_dev,
                                kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers,
-                               p->sliding, p->n_sink, p->window, sl2e);
+                               p->sliding, p->n_sink, p->alibi_slopes, sl2e);
         else
             hipLaunchKernelGGL((decode_partial_bf16_kernel<64, 2>), grid, dim3(256), 0, s, q, a, desc_dev,
                                kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers,
-                               p->sliding, p->n_sink, p->window, sl2e);
+                               p->sliding, p->n_sink, p->alibi_slopes, sl2e);
     } else {
         const float *q = static_cast<const float *>(Q);
-#define RAZOR_F32_ARGS D, grid, s, q, a, desc_dev, kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers, p->sliding, p->n_sink, p->window, sl2e
+#define RAZOR_F32_ARGS D, grid, s, q, a, desc_dev, kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers, p->sliding, p->n_sink, p->alibi_slopes, sl2e
         if (g == 1) launch_partial_f32<1>(RAZOR_F32_ARGS);
         else if (g == 2) launch_partial_f32<2>(RAZOR_F32_ARGS);
         else if (g <= 4) launch_partial_f32<4>(RAZOR_F32_ARGS);
@@ -685,11 +717,11 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
     if (D == 128)
         hipLaunchKernelGGL((combine_kernel<128>), cgrid, dim3(kCombineThreads), 0, s, Q, p->dtype, comp,
                            desc_dev, prefix, nd, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
-                           p->use_comp, p->sliding, p->n_sink, p->window, sl2e);
+                           p->use_comp, p->sliding, p->n_sink, sl2e);
     else
         hipLaunchKernelGGL((combine_kernel<64>), cgrid, dim3(kCombineThreads), 0, s, Q, p->dtype, comp,
                            desc_dev, prefix, nd, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
-                           p->use_comp, p->sliding, p->n_sink, p->window, sl2e);
+                           p->use_comp, p->sliding, p->n_sink, sl2e);
     RAZOR_HIP_CHECK(hipGetLastError());
     return RAZOR_OK;
 }

@@ -42,30 +42,33 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
 struct CachedBlocks {   // rows held this decode step (the token being appended included)
     int has_new;        // a token is appended this step
     int sliding;        // params.sliding
-    int n_sink, window;
+    int n_sink;
 
     // In sliding mode a non-retrieval head that already holds n_sink + window rows keeps that
     // count: the new token overwrites its oldest window row.
-    __device__ __forceinline__ bool slides(int rows, uint32_t flags) const
+    __device__ __forceinline__ bool slides(int rows, uint32_t flags, int window) const
     {
         return has_new && sliding && !(flags & RAZOR_HEAD_RETRIEVAL) && rows >= n_sink + window;
     }
-    __device__ __forceinline__ int rows_of(int rows, int cap, uint32_t flags) const
+    __device__ __forceinline__ int rows_of(int rows, int cap, uint32_t flags, int window) const
     {
-        if (!has_new || slides(rows, flags)) return rows;
+        if (!has_new || slides(rows, flags, window)) return rows;
         return rows < cap ? rows + 1 : rows;   // an append to a full head is skipped
     }
     __device__ __forceinline__ int operator()(const razor_head_desc *__restrict__ desc, int idx) const
     {
-        // {rows, cap, n_dropped, flags}
-        const int4 f = *reinterpret_cast<const int4 *>(reinterpret_cast<const char *>(desc + idx) + 16);
-        return (rows_of(f.x, f.y, (uint32_t)f.w) + kBlockRows - 1) / kBlockRows;
+        const char *e = reinterpret_cast<const char *>(desc + idx);
+        const int4 f = *reinterpret_cast<const int4 *>(e + 16);   // {rows, cap, n_dropped, flags}
+        const int window = *reinterpret_cast<const int *>(e + 36);
+        return (rows_of(f.x, f.y, (uint32_t)f.w, window) + kBlockRows - 1) / kBlockRows;
     }
     // N_d as it counts for this step (the row a sliding head evicts already included)
     __device__ __forceinline__ int step_n_dropped(const razor_head_desc *__restrict__ desc, int idx) const
     {
-        const int4 f = *reinterpret_cast<const int4 *>(reinterpret_cast<const char *>(desc + idx) + 16);
-        return f.z + (slides(f.x, (uint32_t)f.w) ? 1 : 0);
+        const char *e = reinterpret_cast<const char *>(desc + idx);
+        const int4 f = *reinterpret_cast<const int4 *>(e + 16);
+        const int window = *reinterpret_cast<const int *>(e + 36);
+        return f.z + (slides(f.x, (uint32_t)f.w, window) ? 1 : 0);
     }
 };
 struct DroppedBlocks {  // rows Eq.(4) averages

@@ -33,7 +33,12 @@ int check_params(const razor_params *p)
     if (p->n_workers < 0 || p->n_workers > RAZOR_MAX_WORKERS) return RAZOR_EINVAL;
     if ((int64_t)p->batch * p->n_kv_heads > (1 << 20)) return RAZOR_EINVAL;
     if (p->sliding != 0 && p->sliding != 1) return RAZOR_EINVAL;
-    if (p->sliding && p->window < 1) return RAZOR_EINVAL;
+    if (p->reserved0 != 0) return RAZOR_EINVAL;
+    for (int h = 0; h < p->n_kv_heads; ++h) {
+        const int win = p->head_window_host ? p->head_window_host[h] : p->window;
+        if (win < 0 || (p->sliding && win < 1)) return RAZOR_EINVAL;
+    }
+    if (p->alibi_slopes && p->use_comp) return RAZOR_EINVAL;   // a mean of keys has no position
     return RAZOR_OK;
 }
 
@@ -93,13 +98,14 @@ int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *ma
         for (int h = 0; h < p.n_kv_heads; ++h) {
             razor_head_desc &e = desc[(size_t)b * p.n_kv_heads + h];
             const bool retrieval = mask[h] != 0;
+            const int64_t window = p.head_window_host ? p.head_window_host[h] : p.window;
             // Nothing is dropped when sinks and window already cover the sequence: the
             // mean over an empty set in Eq.(4) is undefined, so the head keeps every row.
-            const bool drops = !retrieval && N > (int64_t)p.n_sink + p.window;
-            const int64_t rows = drops ? (int64_t)p.n_sink + p.window : N;
+            const bool drops = !retrieval && N > (int64_t)p.n_sink + window;
+            const int64_t rows = drops ? (int64_t)p.n_sink + window : N;
             int64_t want = rows + p.max_new;
             // a sliding head stops growing at n_sink + window rows
-            if (p.sliding && !retrieval && want > (int64_t)p.n_sink + p.window) want = (int64_t)p.n_sink + p.window;
+            if (p.sliding && !retrieval && want > (int64_t)p.n_sink + window) want = (int64_t)p.n_sink + window;
             const int64_t cap = (int64_t)round_up((size_t)want, kBlockRows);
             if (cap > INT32_MAX) return RAZOR_EINVAL;
             e.row_off = row_off;
@@ -107,6 +113,7 @@ int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *ma
             e.rows = (int32_t)rows;
             e.cap = (int32_t)cap;
             e.n_dropped = drops ? (int32_t)(N - rows) : 0;
+            e.window = (int32_t)window;
             e.flags = (retrieval ? RAZOR_HEAD_RETRIEVAL : 0u) | (drops ? RAZOR_HEAD_COMP : 0u);
             if (e.n_dropped > max_dropped) max_dropped = e.n_dropped;
             row_off += cap;

@@ -364,3 +364,59 @@ def test_sliding_mode_without_compensation_is_sinks_plus_window():
         out = cache.decode(Q, k, v)
         oc.append(k.cpu(), v.cpu())
         check_output(out, oc.decode(Q.cpu(), w.scale, use_comp=False), f"sliding no-comp step {t}")
+
+
+# ----------------------------------------------------------------- ALiBi form (Eq.(1)), per-head buffer lengths
+def alibi_slopes(n_heads):
+    """The usual geometric ALiBi slopes 2^(-8 i / n), i = 1..n."""
+    return (2.0 ** (-8.0 * np.arange(1, n_heads + 1) / n_heads)).astype(np.float32)
+
+
+@pytest.mark.parametrize("cfg,context,batch,sliding,workers,steps", [
+    (1, 1500, 2, False, 0, 20),     # fp32 MHA
+    (2, 2000, 1, False, 0, 20),     # bf16 MHA 32 heads (the Baichuan-style case)
+    (3, 1800, 2, False, 24, 20),    # bf16 GQA: slopes differ inside a group
+    (2, 600, 2, True, 0, 90),       # sliding: short scopes wrap several times
+    (3, 500, 3, True, 16, 70),
+    (1, 400, 1, True, 0, 60),
+])
+def test_alibi_parity(cfg, context, batch, sliding, workers, steps):
+    say(f"alibi parity cfg={cfg} context={context} batch={batch} sliding={sliding} workers={workers} steps={steps}")
+    w = make_workload(cfg, DEV, context=context, batch=batch, max_new=steps)
+    rng = np.random.default_rng(99 + cfg)
+    # per-KV-head vision scopes: a few local heads, a few that keep everything (the "retrieval" heads)
+    hw = rng.choice([17, 48, 100, 10 ** 6], size=w.Hkv).astype(np.int32)
+    hw[0], hw[-1] = 17, 10 ** 6
+    slopes = alibi_slopes(w.Hq)
+    mask = np.zeros(w.Hkv, np.uint8)
+    cache = razor.RazorCache(batch=w.B, n_q_heads=w.Hq, n_kv_heads=w.Hkv, head_dim=w.d, seq_lens=w.seq_lens,
+                             retrieval_mask=mask, n_sink=0, window=0 if not sliding else 1, max_new=steps,
+                             dtype=w.dtype, scale=w.scale, use_comp=False, n_workers=workers, device=DEV,
+                             sliding=sliding, head_window=hw, alibi_slopes=torch.from_numpy(slopes).to(DEV))
+    cache.compress(w.K, w.V)
+    oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, mask, 0, 0, max_new=steps, sliding=sliding,
+                         head_window=hw, alibi_slopes=slopes)
+    np.testing.assert_array_equal(cache.desc()["rows"], oc.rows().reshape(-1))
+    worst = (0.0, 0.0)
+    for t in range(steps):
+        Q, k, v = w.step_inputs(t)
+        out = cache.decode(Q, k, v)
+        oc.append(k.cpu(), v.cpu())
+        e = check_output(out, oc.decode(Q.cpu(), w.scale, use_comp=False), f"alibi step {t}")
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+    np.testing.assert_array_equal(cache.desc()["rows"], oc.rows().reshape(-1))
+    say(f"    {steps} steps: max-abs {worst[0]:.2e}, row-rel {worst[1]:.2e}")
+
+
+def test_alibi_with_sinks_static():
+    say("alibi + sink rows (true prefill distances for the sinks)")
+    w = make_workload(3, DEV, context=900, window=60, batch=2, max_new=10)
+    slopes = alibi_slopes(w.Hq)
+    cache = razor.RazorCache.from_workload(w, use_comp=False, alibi_slopes=torch.from_numpy(slopes).to(DEV))
+    cache.compress(w.K, w.V)
+    oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, w.n_sink, w.window, max_new=10, alibi_slopes=slopes)
+    for t in range(10):
+        Q, k, v = w.step_inputs(t)
+        out = cache.decode(Q, k, v)
+        oc.append(k.cpu(), v.cpu())
+        check_output(out, oc.decode(Q.cpu(), w.scale, use_comp=False), f"alibi sinks step {t}")

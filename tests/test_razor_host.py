@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def params(**kw):
     base = dict(batch=2, n_q_heads=8, n_kv_heads=4, head_dim=128, n_sink=4, window=32, max_new=8,
                 use_comp=1, dtype=razor.RAZOR_BF16, out_dtype=razor.RAZOR_F32, scale=0.088, n_workers=0,
-                sliding=0)
+                sliding=0, reserved0=0, head_window_host=None, alibi_slopes=None)
     base.update(kw)
     return razor.RazorParams(**base)
 
@@ -45,7 +45,7 @@ def test_library_exports_every_declared_symbol():
     assert razor.razor_strerror(razor.RAZOR_OK) == "ok"
     assert "invalid" in razor.razor_strerror(razor.RAZOR_EINVAL)
     assert "workspace" in razor.razor_strerror(razor.RAZOR_ECAPACITY)
-    assert ctypes.sizeof(razor.RazorHeadDesc) == 40 and ctypes.sizeof(razor.RazorParams) == 52
+    assert ctypes.sizeof(razor.RazorHeadDesc) == 40 and ctypes.sizeof(razor.RazorParams) == 72
 
 
 @pytest.mark.parametrize("seq_lens,mask,n_sink,window", [
@@ -100,6 +100,7 @@ def test_plan_reproduces_table2_ratio():
     dict(n_sink=-1), dict(window=-1), dict(max_new=-1), dict(dtype=2), dict(out_dtype=7),
     dict(use_comp=2), dict(scale=0.0), dict(scale=float("nan")), dict(n_workers=-1),
     dict(n_workers=razor.RAZOR_MAX_WORKERS + 1), dict(sliding=2), dict(sliding=1, window=0),
+    dict(reserved0=1), dict(alibi_slopes=4096),          # slopes with use_comp = 1
 ])
 def test_bad_params_are_rejected(kw):
     p = params(**kw)
@@ -156,3 +157,23 @@ def test_plan_sliding_mode_caps_the_window_heads():
     assert (desc["evicted"] == 0).all()
     # the sinks must lie inside the prefill
     assert plan(p, [500, 3, 36], [0, 1], want_idx=False)[0] == razor.RAZOR_EINVAL
+
+
+def test_plan_per_head_windows_match_oracle():
+    # ALiBi models: one buffer length (vision scope) per KV head, no sinks
+    hw = np.array([5, 1000, 64, 0], np.int32)
+    p = params(batch=2, n_kv_heads=4, n_q_heads=8, n_sink=0, window=7, use_comp=0, head_window_host=hw.ctypes.data)
+    rc, desc, idx, sizes = plan(p, [300, 40], [0, 0, 0, 0])
+    assert rc == razor.RAZOR_OK
+    total = 0
+    for b, N in enumerate([300, 40]):
+        for h in range(4):
+            e = desc[b * 4 + h]
+            kept, lo, hi = orc.select(N, False, 0, int(hw[h]))
+            assert e["rows"] == len(kept) and e["n_dropped"] == hi - lo and e["window"] == hw[h]
+            np.testing.assert_array_equal(idx[total: total + len(kept)], kept)
+            total += len(kept)
+    assert desc["rows"].reshape(2, 4).tolist() == [[5, 300, 64, 0], [5, 40, 40, 0]]
+    hw_bad = np.array([5, -1, 64, 0], np.int32)
+    assert razor.razor_plan(params(n_kv_heads=4, head_window_host=hw_bad.ctypes.data), np.array([300, 40], np.int32),
+                            np.zeros(4, np.uint8), None, None, razor.RazorSizes()) == razor.RAZOR_EINVAL
