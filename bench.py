@@ -193,6 +193,8 @@ def main():
     ap.add_argument("--no-full", action="store_true", help="skip the uncompressed-cache comparison")
     ap.add_argument("--sliding", action="store_true", help="decode in sliding mode (window heads evict "
                     "their oldest row into the compensation token instead of growing)")
+    ap.add_argument("--alibi", action="store_true", help="ALiBi form: Eq.(1) logit bias, no sinks, no "
+                    "compensation token, per-head buffer lengths (retrieval heads keep everything)")
     ap.add_argument("--pmc-calib", action="store_true", help="also run one plain 1 GiB device copy, the "
                     "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
@@ -223,13 +225,19 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     lib = razor.load_library()
 
+    extra = {}
+    if args.alibi:
+        w.n_sink = 0
+        slopes = (2.0 ** (-8.0 * np.arange(1, w.Hq + 1) / w.Hq)).astype(np.float32)
+        extra = dict(use_comp=False, alibi_slopes=torch.from_numpy(slopes).to(dev))
+
     def build_caches(mask, n):
         caches = []
         for _ in range(n):
             c = razor.RazorCache(batch=w.B, n_q_heads=w.Hq, n_kv_heads=w.Hkv, head_dim=w.d,
                                  seq_lens=w.seq_lens, retrieval_mask=mask, n_sink=w.n_sink,
                                  window=w.window, max_new=max_new, dtype=w.dtype, scale=w.scale,
-                                 n_workers=args.workers, device=dev, sliding=args.sliding)
+                                 n_workers=args.workers, device=dev, sliding=args.sliding, **extra)
             c.compress(w.K, w.V)
             caches.append(c)
         torch.cuda.synchronize()
@@ -276,7 +284,7 @@ def main():
     if args.sliding:   # window heads stay at n_sink + window rows
         stay = (desc0["flags"] & razor.RAZOR_HEAD_RETRIEVAL) == 0
         desc_avg["rows"][stay] = np.minimum(desc_avg["rows"][stay], w.n_sink + w.window)
-    step_bytes = algorithmic_bytes_decode(desc_avg, w.d, esize, w.B, w.Hq)
+    step_bytes = algorithmic_bytes_decode(desc_avg, w.d, esize, w.B, w.Hq, use_comp=not args.alibi)
     gbps = step_bytes / (wall / args.steps) / 1e9
     kernel_gbps = step_bytes / (kernel_ms * 1e-3) / 1e9
 
@@ -353,7 +361,7 @@ def main():
         "config": {"workload": f"BASELINE config {args.config}: {w.name}, batch {w.B}, {w.Hq} query / "
                                f"{w.Hkv} KV heads, head_dim {w.d}, context {w.N}, window {w.window}, "
                                f"{w.n_sink} sinks, {int(w.mask.sum())} retrieval KV heads; one step = "
-                               "append one token + compressed decode attention + combine" + (" (sliding mode)" if args.sliding else ""),
+                               "append one token + compressed decode attention + combine" + (" (sliding mode)" if args.sliding else "") + (" (ALiBi logits, no sinks, no compensation token)" if args.alibi else ""),
                    "cached_rows": kept_rows, "full_rows": full_rows, "copies_rotated": args.copies},
         "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
         "step_bytes": step_bytes,
