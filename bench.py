@@ -193,6 +193,8 @@ def main():
     ap.add_argument("--no-full", action="store_true", help="skip the uncompressed-cache comparison")
     ap.add_argument("--sliding", action="store_true", help="decode in sliding mode (window heads evict "
                     "their oldest row into the compensation token instead of growing)")
+    ap.add_argument("--graph", action="store_true", help="time replays of a HIP graph holding one decode "
+                    "step per rotated cache (removes host launch overhead; matters for small configs)")
     ap.add_argument("--alibi", action="store_true", help="ALiBi form: Eq.(1) logit bias, no sinks, no "
                     "compensation token, per-head buffer lengths (retrieval heads keep everything)")
     ap.add_argument("--pmc-calib", action="store_true", help="also run one plain 1 GiB device copy, the "
@@ -219,7 +221,7 @@ def main():
         return run_stack(args, ev)
 
     total_steps = args.steps + args.warmup
-    max_new = 2 * (total_steps // args.copies + 2)           # timed pass + kernel-timing pass
+    max_new = 3 * (total_steps // args.copies + 4)           # timed pass + kernel-timing pass (+ graph warm-up)
     w = make_workload(args.config, dev, max_new=max_new)
     esize = 4 if w.dtype == torch.float32 else 2
     stream = torch.cuda.current_stream().cuda_stream
@@ -247,8 +249,32 @@ def main():
     inputs = [w.step_inputs(t) for t in range(8)]
     out = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=dev)
 
+    def run_graph(caches, n):
+        """n decode steps as replays of one captured graph (one step per cache)."""
+        Q, k, v = inputs[0]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            caches[0].decode(Q, k, v, out=out)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for c in caches:
+                c.decode(Q, k, v, out=out)
+        reps = max(1, n // len(caches))
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * n / (reps * len(caches)), None
+
     def run(caches, n, profile=False):
         """n decode steps; returns (wall seconds, mean ms of the partial kernel or None)."""
+        if args.graph and not profile:
+            return run_graph(caches, n)
         pairs = []
         torch.cuda.synchronize()
         t0 = time.perf_counter()
