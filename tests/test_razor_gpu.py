@@ -453,3 +453,50 @@ def test_decode_under_hip_graph_capture_matches_eager():
         assert torch.equal(out_g, ref), f"replay {t}"
         _ = (w.K[0, 0, :64].float().sum()).item()          # unrelated eager work between replays
     np.testing.assert_array_equal(graphed.desc()["rows"], eager.desc()["rows"])
+
+
+# ----------------------------------------------------------------- group sizes and head dims
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64), (torch.float32, 128)])
+@pytest.mark.parametrize("g", [2, 3, 5, 16])
+def test_every_group_size_and_head_dim(dtype, d, g):
+    say(f"group size {g}, head_dim {d}, {dtype}")
+    Hkv, B, N = 3, 2, 1100
+    gen = torch.Generator(device=DEV); gen.manual_seed(1234 + g + d)
+    K = torch.randn(B, Hkv, N, d, generator=gen, device=DEV).to(dtype)
+    V = torch.randn(B, Hkv, N, d, generator=gen, device=DEV).to(dtype)
+    seq, mask = np.array([1100, 777], np.int32), np.array([0, 1, 0], np.uint8)
+    cache = razor.RazorCache(batch=B, n_q_heads=Hkv * g, n_kv_heads=Hkv, head_dim=d, seq_lens=seq,
+                             retrieval_mask=mask, n_sink=4, window=150, max_new=4, dtype=dtype, device=DEV)
+    cache.compress(K, V)
+    oc = orc.OracleCache(K.cpu(), V.cpu(), seq, mask, 4, 150, max_new=4)
+    for t in range(4):
+        Q = torch.randn(B, Hkv * g, d, generator=gen, device=DEV).to(dtype)
+        k = torch.randn(B, Hkv, d, generator=gen, device=DEV).to(dtype)
+        v = torch.randn(B, Hkv, d, generator=gen, device=DEV).to(dtype)
+        out = cache.decode(Q, k, v)
+        oc.append(k.cpu(), v.cpu())
+        check_output(out, oc.decode(Q.cpu(), d ** -0.5), f"g={g} d={d} step {t}")
+
+
+def test_many_heads():
+    say("1000 (sequence, head) pairs: the block-prefix scans run over 16 chunks of 64 heads")
+    B, Hkv, g, d, N = 125, 8, 2, 64, 96
+    gen = torch.Generator(device=DEV); gen.manual_seed(4321)
+    K = torch.randn(B, Hkv, N, d, generator=gen, device=DEV).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, N, d, generator=gen, device=DEV).to(torch.bfloat16)
+    seq = np.random.default_rng(3).integers(1, N + 1, size=B).astype(np.int32)
+    mask = np.array([0, 1, 0, 0, 0, 0, 1, 0], np.uint8)
+    cache = razor.RazorCache(batch=B, n_q_heads=Hkv * g, n_kv_heads=Hkv, head_dim=d, seq_lens=seq,
+                             retrieval_mask=mask, n_sink=2, window=20, max_new=3, dtype=torch.bfloat16, device=DEV)
+    cache.compress(K, V)
+    oc = orc.OracleCache(K.cpu(), V.cpu(), seq, mask, 2, 20, max_new=3)
+    comp = cache.comp.cpu().numpy().reshape(B, Hkv, 2, d).astype(np.float64)
+    np.testing.assert_allclose(comp[:, :, 0], oc.khat, rtol=0, atol=2e-5)
+    for t in range(3):
+        Q = torch.randn(B, Hkv * g, d, generator=gen, device=DEV).to(torch.bfloat16)
+        k = torch.randn(B, Hkv, d, generator=gen, device=DEV).to(torch.bfloat16)
+        v = torch.randn(B, Hkv, d, generator=gen, device=DEV).to(torch.bfloat16)
+        out = cache.decode(Q, k, v)
+        oc.append(k.cpu(), v.cpu())
+        check_output(out, oc.decode(Q.cpu(), d ** -0.5), f"many heads step {t}")
+    np.testing.assert_array_equal(cache.desc()["rows"], oc.rows().reshape(-1))
