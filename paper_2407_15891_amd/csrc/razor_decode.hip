@@ -136,6 +136,17 @@ struct RowDistance {
         else dist = rows - 1 - row;
         return (float)dist;
     }
+    // Most blocks lie on one straight piece of that map: distance(row) = A - row for every row
+    // of block t (no sink row, not the block where the ring wraps).  Returns false otherwise.
+    __device__ __forceinline__ bool linear(int t, int &A) const
+    {
+        const int lo = t * kBlockRows, hi = lo + kBlockRows - 1;
+        if (lo < n_sink) return false;
+        if (newest < 0) { A = rows - 1; return true; }
+        if (hi <= newest) { A = newest; return true; }
+        if (lo > newest) { A = newest + window; return true; }
+        return false;
+    }
 };
 
 // ---------------------------------------------------------------- partial, bf16 / matrix cores
@@ -251,9 +262,21 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
             const int row0 = t * kBlockRows + 4 * kg;
             float bmax = kNegInf;
 #pragma unroll
+            for (int r = 0; r < 4; ++r) sv[r] = S[r] * scale_log2e;
+            if (slopes) {   // Eq.(1): minus slope * distance to the query
+                int A;
+                if (distance.linear(t, A)) {
+                    const float c0 = slope_l2e * (float)(A - row0);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sv[r] -= c0 - slope_l2e * (float)r;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sv[r] -= slope_l2e * distance(row0 + r);
+                }
+            }
+#pragma unroll
             for (int r = 0; r < 4; ++r) {
-                sv[r] = row0 + r < rows ? S[r] * scale_log2e : kNegInf;
-                if (slopes) sv[r] -= slope_l2e * distance(row0 + r);
+                sv[r] = row0 + r < rows ? sv[r] : kNegInf;
                 bmax = fmaxf(bmax, sv[r]);
             }
             bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
