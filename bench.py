@@ -201,8 +201,8 @@ def main():
                     "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); the path shards by KV head "
-              "and batch with no exchange, see DESIGN.md", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (--gpus 1); the path would shard by KV head "
+              "and batch with no exchange between GPUs", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
