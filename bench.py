@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the RazorAttention hot path on one MI355X.
 
-Workload (default): BASELINE config 3 -- a Llama-3-8B-shaped GQA layer, batch 4, 32 query
+Workload (default): benchmark configuration 3 -- a Llama-3-8B-shaped GQA layer, batch 4, 32 query
 heads over 8 KV heads, head_dim 128, context 131072, bf16, 2 of 8 KV heads retrieval,
 window max(4096, 15 % of context) + 4 sinks + compensation token.  Seeded synthetic data.
 
@@ -86,7 +86,7 @@ class HipEvents:
 
 
 def run_stack(args, ev):
-    """BASELINE config 5: a 32-layer 8B-shaped stack (GQA 32/8 x 128, bf16), batch 8, context
+    """benchmark configuration 5: a 32-layer 8B-shaped stack (GQA 32/8 x 128, bf16), batch 8, context
     131072; per-layer seeded retrieval masks (38 of 256 (layer, KV head) pairs).  Compress every
     layer after a synthetic prefill, then `steps` decode steps, each one razor_decode_attn per
     layer with an append.  The full-cache run uses the same kernels with every head retrieval."""
@@ -159,7 +159,7 @@ def run_stack(args, ev):
         "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warm,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"BASELINE config 5: {L}-layer 8B-shaped stack, GQA {w.Hq}/{w.Hkv} x {w.d}, "
+        "config": {"workload": f"benchmark configuration 5: {L}-layer 8B-shaped stack, GQA {w.Hq}/{w.Hkv} x {w.d}, "
                                f"batch {w.B}, context {w.N}, window {w.window}, {w.n_sink} sinks, "
                                f"{int(sum(m.sum() for m in masks))} retrieval (layer, KV head) pairs; one step = "
                                f"{L} x (append + compressed decode attention + combine)",
@@ -384,7 +384,7 @@ def main():
         "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32", "data": "synthetic",
-        "config": {"workload": f"BASELINE config {args.config}: {w.name}, batch {w.B}, {w.Hq} query / "
+        "config": {"workload": f"benchmark configuration {args.config}: {w.name}, batch {w.B}, {w.Hq} query / "
                                f"{w.Hkv} KV heads, head_dim {w.d}, context {w.N}, window {w.window}, "
                                f"{w.n_sink} sinks, {int(w.mask.sum())} retrieval KV heads; one step = "
                                "append one token + compressed decode attention + combine" + (" (sliding mode)" if args.sliding else "") + (" (ALiBi logits, no sinks, no compensation token)" if args.alibi else ""),
