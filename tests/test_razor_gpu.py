@@ -500,3 +500,46 @@ def test_many_heads():
         oc.append(k.cpu(), v.cpu())
         check_output(out, oc.decode(Q.cpu(), d ** -0.5), f"many heads step {t}")
     np.testing.assert_array_equal(cache.desc()["rows"], oc.rows().reshape(-1))
+
+
+# ----------------------------------------------------------------- seeded random sweep
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_shapes_parity(seed):
+    """Random but seeded shapes: batch, heads, group, head_dim, dtype, ragged lengths, sinks,
+    window (global or per head), workers, static / sliding, with and without compensation."""
+    rng = np.random.default_rng(5000 + seed)
+    dtype = torch.bfloat16 if rng.random() < 0.6 else torch.float32
+    d = int(rng.choice([64, 128]))
+    B, Hkv, g = int(rng.integers(1, 5)), int(rng.integers(1, 6)), int(rng.choice([1, 2, 4, 7, 8]))
+    N = int(rng.choice([40, 200, 1000, 3000]))
+    n_sink = int(rng.choice([0, 2, 4]))
+    sliding = bool(rng.integers(0, 2))
+    window = int(rng.choice([1, 5, 16, 37, 250]))
+    use_comp = bool(rng.random() < 0.8)
+    steps = int(rng.choice([3, 25]))
+    workers = int(rng.choice([0, 4, 12, 200]))
+    lens = rng.integers(max(1, n_sink), N + 1, size=B).astype(np.int32)
+    mask = (rng.random(Hkv) < 0.3).astype(np.uint8)
+    hw = rng.choice([1, 7, 64, 10 ** 6], size=Hkv).astype(np.int32) if rng.random() < 0.3 else None
+    say(f"random seed={seed}: {dtype} d={d} B={B} Hkv={Hkv} g={g} N={N} lens={lens.tolist()} sinks={n_sink} "
+        f"window={window} head_window={None if hw is None else hw.tolist()} sliding={sliding} comp={use_comp} "
+        f"workers={workers} steps={steps}")
+    gen = torch.Generator(device=DEV); gen.manual_seed(9000 + seed)
+    K = torch.randn(B, Hkv, N, d, generator=gen, device=DEV).to(dtype)
+    V = torch.randn(B, Hkv, N, d, generator=gen, device=DEV).to(dtype)
+    cache = razor.RazorCache(batch=B, n_q_heads=Hkv * g, n_kv_heads=Hkv, head_dim=d, seq_lens=lens,
+                             retrieval_mask=mask, n_sink=n_sink, window=window, max_new=steps, dtype=dtype,
+                             use_comp=use_comp, n_workers=workers, device=DEV, sliding=sliding, head_window=hw)
+    cache.compress(K, V)
+    oc = orc.OracleCache(K.cpu(), V.cpu(), lens, mask, n_sink, window, max_new=steps, sliding=sliding, head_window=hw)
+    for t in range(steps):
+        Q = torch.randn(B, Hkv * g, d, generator=gen, device=DEV).to(dtype)
+        k = torch.randn(B, Hkv, d, generator=gen, device=DEV).to(dtype)
+        v = torch.randn(B, Hkv, d, generator=gen, device=DEV).to(dtype)
+        out = cache.decode(Q, k, v)
+        oc.append(k.cpu(), v.cpu())
+        check_output(out, oc.decode(Q.cpu(), d ** -0.5, use_comp=use_comp), f"seed {seed} step {t}")
+    dsc = cache.desc()
+    np.testing.assert_array_equal(dsc["rows"], oc.rows().reshape(-1))
+    np.testing.assert_array_equal(dsc["n_dropped"], oc.N_d.reshape(-1))
+    assert not (dsc["flags"] & razor.RAZOR_HEAD_OVERFLOW).any()

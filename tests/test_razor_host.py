@@ -177,3 +177,36 @@ def test_plan_per_head_windows_match_oracle():
     hw_bad = np.array([5, -1, 64, 0], np.int32)
     assert razor.razor_plan(params(n_kv_heads=4, head_window_host=hw_bad.ctypes.data), np.array([300, 40], np.int32),
                             np.zeros(4, np.uint8), None, None, razor.RazorSizes()) == razor.RAZOR_EINVAL
+
+
+def test_plan_random_tables_match_oracle():
+    """Seeded sweep over lengths, masks, sinks, windows (global and per head), static and sliding."""
+    rng = np.random.default_rng(2024)
+    for trial in range(300):
+        B, H = int(rng.integers(1, 6)), int(rng.integers(1, 9))
+        n_sink = int(rng.choice([0, 1, 4, 9]))
+        sliding = int(rng.integers(0, 2))
+        window = int(rng.choice([1, 2, 15, 16, 17, 100, 5000]))
+        lens = rng.integers(max(1, n_sink if sliding else 1), 400, size=B).astype(np.int32)
+        mask = (rng.random(H) < 0.3).astype(np.uint8)
+        hw = rng.choice([1, 3, 16, 64, 10 ** 6], size=H).astype(np.int32) if rng.random() < 0.4 else None
+        max_new = int(rng.choice([0, 1, 33]))
+        p = params(batch=B, n_kv_heads=H, n_q_heads=H * int(rng.choice([1, 2, 4])), n_sink=n_sink, window=window,
+                   max_new=max_new, sliding=sliding, head_window_host=None if hw is None else hw.ctypes.data)
+        rc, desc, idx, sizes = plan(p, lens, mask)
+        assert rc == razor.RAZOR_OK, trial
+        total, off = 0, 0
+        for b in range(B):
+            for h in range(H):
+                e = desc[b * H + h]
+                win = window if hw is None else int(hw[h])
+                kept, lo, hi = orc.select(int(lens[b]), bool(mask[h]), n_sink, win)
+                assert e["rows"] == len(kept) and e["n_dropped"] == hi - lo and e["window"] == win, trial
+                np.testing.assert_array_equal(idx[total: total + len(kept)], kept)
+                assert e["row_off"] == off and e["cap"] % 16 == 0 and e["cap"] >= e["rows"]
+                grow = e["rows"] + max_new
+                if sliding and not mask[h]:
+                    grow = min(grow, n_sink + win)
+                assert grow <= e["cap"] < grow + 16, trial
+                total += len(kept); off += e["cap"]
+        assert sizes.total_rows == total and sizes.total_cap == off
