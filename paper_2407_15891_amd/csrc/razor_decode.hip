@@ -71,7 +71,9 @@ __device__ __forceinline__ void append_row(const razor_head_desc &e, int head, c
         const uint4 v = *reinterpret_cast<const uint4 *>(v_new + (int64_t)head * RB + piece * 16);
         *reinterpret_cast<uint4 *>(vplane + (int64_t)t * RB + piece * 16) = v;
     }
-    __threadfence();   // the loads of this wave that follow must see the row
+    // Only this wave reads the row again in this launch: the store has to be complete before
+    // those loads are issued, nothing has to be made visible to other compute units.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 }
 
 // Sliding mode, head full: row `slot` (the oldest window row) first moves into the
@@ -111,7 +113,8 @@ __device__ __forceinline__ void evict_row(const razor_head_desc &e, int head, in
         *reinterpret_cast<uint4 *>(pos) =
             *reinterpret_cast<const uint4 *>((which ? v_new : k_new) + (int64_t)head * RB + piece * 16);
     }
-    __threadfence();   // the loads of this wave that follow must see the new row
+    // Only this wave reads the row again in this launch (comp is read by the next kernel).
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
 }
 
 // ALiBi (Eq.(1)): how far behind the query (the newest token) cache row `row` lies.
@@ -199,17 +202,34 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
     locate_block(count, desc, n_heads, lane, lo, i, first);
     RAZOR_STAMP(1);
 
-    while (lo < hi) {
-        razor_head_desc e = desc[i];
-        int rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
-        while (first + (rows + kBlockRows - 1) / kBlockRows <= lo) {   // heads without a block here
-            first += (rows + kBlockRows - 1) / kBlockRows;
-            e = desc[++i];
-            rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
+    // The query group of head `head` as B operand of the first product (zero rows pad the group).
+    auto load_query = [&](int head, bf16x8(&q)[NS]) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            uint4 qv = make_uint4(0, 0, 0, 0);
+            if (n < g)
+                qv = *reinterpret_cast<const uint4 *>(Q + ((int64_t)head * g + n) * D + (4 * s + kg) * 8);
+            q[s] = __builtin_bit_cast(bf16x8, qv);
         }
+    };
+    razor_head_desc e = desc[i];   // head i owns block lo (locate_block never returns an empty head)
+    bf16x8 qreg[NS];
+    load_query(i, qreg);
+
+    while (lo < hi) {
+        const int rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
         const int head_end = first + (rows + kBlockRows - 1) / kBlockRows;
         const int seg_end = hi < head_end ? hi : head_end;
-        const int b = i / n_kv_heads, h = i % n_kv_heads;
+        // A range that runs past this head continues in the next one: fetch that head's entry and
+        // query group now, so that the switch does not wait for them.
+        const bool more = seg_end < hi;
+        razor_head_desc e_next = e;
+        bf16x8 q_next[NS];
+        if (more) {
+            e_next = desc[i + 1];
+            load_query(i + 1, q_next);
+        }
+        const int h = i % n_kv_heads;
         char *kplane = arena + e.row_off * 2 * RB;
         char *vplane = kplane + (int64_t)e.cap * RB;
         if (has_new) {   // the wave that owns the block of the row the new token goes to stores it
@@ -219,16 +239,6 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
                 if (slides) evict_row<RB, RAZOR_BF16>(e, i, slot, kplane, vplane, k_new, v_new, comp, lane);
                 else append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
             }
-        }
-
-        bf16x8 qreg[NS];
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            uint4 qv = make_uint4(0, 0, 0, 0);
-            if (n < g)
-                qv = *reinterpret_cast<const uint4 *>(
-                    Q + ((int64_t)(b * n_kv_heads + h) * g + n) * D + (4 * s + kg) * 8);
-            qreg[s] = __builtin_bit_cast(bf16x8, qv);
         }
 
         const bool slides_now = count.slides(e.rows, e.flags, e.window);
@@ -347,6 +357,17 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
         }
         lo = seg_end;
         RAZOR_STAMP_SEG();
+        if (more) {
+            first = head_end;
+            e = e_next;
+            ++i;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) qreg[s] = q_next[s];
+            while (count.rows_of(e.rows, e.cap, e.flags, e.window) == 0) {   // heads that hold no row
+                e = desc[++i];
+                load_query(i, qreg);
+            }
+        }
     }
     RAZOR_STAMP(2);
     RAZOR_STAMP_FLUSH();
