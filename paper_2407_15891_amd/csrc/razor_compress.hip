@@ -76,14 +76,10 @@ __global__ __launch_bounds__(256) void mean_stream_kernel(
     const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int prow = lane / LPR, piece = lane % LPR;
     const DroppedBlocks count;
-    const int total = total_blocks(count, desc, n_heads, lane);
-    const int per = blocks_per_worker(total, n_workers);
+    int total, per, lo, hi, i, first;
+    plan_range(count, desc, n_heads, n_workers, w, lane, total, per, lo, hi, i, first);
     if (w == 0) write_prefix(count, desc, n_heads, lane, per, prefix);
-    int lo = w * per;
-    const int hi = lo + per < total ? lo + per : total;
     if (lo >= hi) return;
-    int i, first;
-    locate_block(count, desc, n_heads, lane, lo, i, first);
 
     while (lo < hi) {
         razor_head_desc e = desc[i];

@@ -189,17 +189,13 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
 #endif
     RAZOR_STAMP(0);
     const CachedBlocks count{has_new, sliding, n_sink};
-    const int total = total_blocks(count, desc, n_heads, lane);
-    const int per = blocks_per_worker(total, n_workers);
+    int total, per, lo, hi, i, first;
+    plan_range(count, desc, n_heads, n_workers, w, lane, total, per, lo, hi, i, first);
     if (w == 0) {   // what the combine kernel needs, taken before anything is committed
         write_prefix(count, desc, n_heads, lane, per, prefix);
         for (int idx = lane; idx < n_heads; idx += 64) nd_step[idx] = count.step_n_dropped(desc, idx);
     }
-    int lo = w * per;
-    const int hi = lo + per < total ? lo + per : total;
     if (lo >= hi) return;
-    int i, first;
-    locate_block(count, desc, n_heads, lane, lo, i, first);
     RAZOR_STAMP(1);
 
     // The query group of head `head` as B operand of the first product (zero rows pad the group).
@@ -405,17 +401,13 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
 #endif
     RAZOR_STAMP(0);
     const CachedBlocks count{has_new, sliding, n_sink};
-    const int total = total_blocks(count, desc, n_heads, lane);
-    const int per = blocks_per_worker(total, n_workers);
+    int total, per, lo, hi, i, first;
+    plan_range(count, desc, n_heads, n_workers, w, lane, total, per, lo, hi, i, first);
     if (w == 0) {   // what the combine kernel needs, taken before anything is committed
         write_prefix(count, desc, n_heads, lane, per, prefix);
         for (int idx = lane; idx < n_heads; idx += 64) nd_step[idx] = count.step_n_dropped(desc, idx);
     }
-    int lo = w * per;
-    const int hi = lo + per < total ? lo + per : total;
     if (lo >= hi) return;
-    int i, first;
-    locate_block(count, desc, n_heads, lane, lo, i, first);
     RAZOR_STAMP(1);
 
     while (lo < hi) {

@@ -119,6 +119,35 @@ __device__ __forceinline__ void locate_block(F count, const razor_head_desc *__r
     }
 }
 
+// Wave-cooperative.  Everything a worker needs in one go: the length of the axis, the blocks
+// per worker, this worker's range [lo, hi) and, if that range is not empty, the head that owns
+// block lo with the flattened index of its first block.  With at most 64 heads (the usual
+// case) one load and one scan serve all of it.
+template <class F>
+__device__ __forceinline__ void plan_range(F count, const razor_head_desc *__restrict__ desc,
+                                           int n_heads, int n_workers, int w, int lane, int &total,
+                                           int &per, int &lo, int &hi, int &head, int &first)
+{
+    if (n_heads <= 64) {
+        const int nb = lane < n_heads ? count(desc, lane) : 0;
+        const int end = wave_inclusive_scan(nb, lane);
+        total = __shfl(end, 63);
+        per = blocks_per_worker(total, n_workers);
+        lo = w * per;
+        hi = lo + per < total ? lo + per : total;
+        const int c = __popcll(__ballot(end <= lo));
+        head = c;
+        first = c == 0 ? 0 : __shfl(end, c - 1);
+        return;
+    }
+    total = total_blocks(count, desc, n_heads, lane);
+    per = blocks_per_worker(total, n_workers);
+    lo = w * per;
+    hi = lo + per < total ? lo + per : total;
+    head = first = 0;
+    if (lo < hi) locate_block(count, desc, n_heads, lane, lo, head, first);
+}
+
 // Wave-cooperative.  prefix[i] = flattened index of head i's first block, prefix[n_heads] =
 // length of the axis, prefix[n_heads + 1] = blocks per worker: what a later kernel needs to
 // find the partial results of a head (segment of worker w in head i -> slot w + i).
