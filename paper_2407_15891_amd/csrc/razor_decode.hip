@@ -554,8 +554,9 @@ __device__ __forceinline__ float load_q(const void *Q, int dtype, int64_t idx)
 }
 
 // One workgroup per query head.  Eq.(5): the compensation token is one more softmax
-// entry with logit scale * q.khat + ln N_d and value vhat; the partial states of the
-// head's segments are merged around the common maximum in slot order.
+// entry with logit scale * q.khat + ln N_d and value vhat.  The partial states of the head's
+// segments are merged in one pass: 32 slot groups each fold their slots (in slot order) into
+// a running state, the 32 states are merged around their common maximum in group order.
 constexpr int kCombineThreads = 1024;
 
 template <int D>
@@ -568,10 +569,9 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
 {
     constexpr int C4 = D / 4;                    // float4 columns
     constexpr int GR = kCombineThreads / C4;     // slot groups working in parallel
-    constexpr int NW = kCombineThreads / 64;
-    __shared__ float s_red[NW];
+    __shared__ float s_comp;
+    __shared__ float s_m[GR], s_l[GR];
     __shared__ float4 s_acc[GR][C4];
-    __shared__ float s_den[GR];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n_q_heads = n_kv_heads * g;
     const int bj = blockIdx.x, b = bj / n_q_heads, j = bj % n_q_heads;
@@ -579,64 +579,66 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
     const razor_head_desc e = desc[i];
     const int n_dropped = nd_step[i];   // N_d of this step (a row evicted this step included)
     const bool has_comp = use_comp && n_dropped > 0;
-
-    if (wave == 0) {   // q . khat
-        float part = 0.f;
-        if (has_comp)
-            for (int c = lane; c < D; c += 64)
-                part += load_q(Q, q_dtype, (int64_t)bj * D + c) * comp[(size_t)i * 2 * D + c];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
-        if (lane == 0) s_red[0] = part;
-    }
-    __syncthreads();
     const int first = prefix[i], last = prefix[i + 1], per = prefix[n_heads + 1];
     const int w0 = first / per;
     const int n_slots = last > first ? (last - 1) / per - w0 + 1 : 0;
-    const float m_comp = has_comp ? s_red[0] * scale_log2e + log2f((float)n_dropped) : kNegInf;
-    __syncthreads();
 
-    float mx = m_comp;
-    for (int s = tid; s < n_slots; s += kCombineThreads)
-        mx = fmaxf(mx, part_ml[((size_t)(w0 + s + i) * g + n) * 2]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    if (lane == 0) s_red[wave] = mx;
-    __syncthreads();
-    float M = s_red[0];
-#pragma unroll
-    for (int k = 1; k < NW; ++k) M = fmaxf(M, s_red[k]);
+    // wave 0 starts q . khat; its loads travel together with the partial states below
+    float dot = 0.f;
+    if (wave == 0 && has_comp)
+        for (int c = lane; c < D; c += 64)
+            dot += load_q(Q, q_dtype, (int64_t)bj * D + c) * comp[(size_t)i * 2 * D + c];
 
+    // every slot group folds its share of the head's partial states into one running state
     const int col = tid % C4, grp = tid / C4;
+    float mg = kNegInf, lg = 0.f;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-    float den = 0.f;
     for (int s = grp; s < n_slots; s += GR) {
         const size_t slot = (size_t)(w0 + s + i) * g + n;
         const float2 ml = *reinterpret_cast<const float2 *>(part_ml + slot * 2);
         const float4 v = *reinterpret_cast<const float4 *>(part_acc + slot * D + 4 * col);
-        const float wgt = fast_exp2(ml.x - M);
-        a.x += wgt * v.x; a.y += wgt * v.y; a.z += wgt * v.z; a.w += wgt * v.w;
-        den += wgt * ml.y;
+        const float m_new = fmaxf(mg, ml.x);
+        const float so = fast_exp2(mg - m_new), sn = fast_exp2(ml.x - m_new);   // mg = -inf gives 0
+        a.x = a.x * so + v.x * sn; a.y = a.y * so + v.y * sn;
+        a.z = a.z * so + v.z * sn; a.w = a.w * so + v.w * sn;
+        lg = lg * so + ml.y * sn;
+        mg = m_new;
     }
-    if (grp == 0 && has_comp) {
-        const float wgt = fast_exp2(m_comp - M);
-        const float4 v = *reinterpret_cast<const float4 *>(comp + ((size_t)i * 2 + 1) * D + 4 * col);
-        a.x += wgt * v.x; a.y += wgt * v.y; a.z += wgt * v.z; a.w += wgt * v.w;
-        den += wgt;
+    if (wave == 0) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+        if (lane == 0) s_comp = dot;
     }
     s_acc[grp][col] = a;
-    if (col == 0) s_den[grp] = den;
+    if (col == 0) {
+        s_m[grp] = mg;
+        s_l[grp] = lg;
+    }
     __syncthreads();
     if (grp == 0) {
-        float dsum = 0.f;
-        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+        // Eq.(5): the compensation token is one more entry, logit scale * q.khat + ln N_d, value vhat
+        const float m_comp = has_comp ? s_comp * scale_log2e + log2f((float)n_dropped) : kNegInf;
+        float M = m_comp;
 #pragma unroll 8
-        for (int k = 0; k < GR; ++k) {
-            const float4 v = s_acc[k][col];
-            num.x += v.x; num.y += v.y; num.z += v.z; num.w += v.w;
-            dsum += s_den[k];
+        for (int k = 0; k < GR; ++k) M = fmaxf(M, s_m[k]);
+        float den = 0.f;
+        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (M > kNegInf) {
+#pragma unroll 8
+            for (int k = 0; k < GR; ++k) {
+                const float wgt = fast_exp2(s_m[k] - M);   // empty groups: exp2(-inf) = 0
+                const float4 v = s_acc[k][col];
+                num.x += wgt * v.x; num.y += wgt * v.y; num.z += wgt * v.z; num.w += wgt * v.w;
+                den += wgt * s_l[k];
+            }
+            if (has_comp) {
+                const float wgt = fast_exp2(m_comp - M);
+                const float4 v = *reinterpret_cast<const float4 *>(comp + ((size_t)i * 2 + 1) * D + 4 * col);
+                num.x += wgt * v.x; num.y += wgt * v.y; num.z += wgt * v.z; num.w += wgt * v.w;
+                den += wgt;
+            }
         }
-        const float inv = dsum > 0.f ? 1.f / dsum : 0.f;   // a head with no entry at all gives zeros
+        const float inv = den > 0.f ? 1.f / den : 0.f;   // a head with no entry at all gives zeros
         num.x *= inv; num.y *= inv; num.z *= inv; num.w *= inv;
         if (out_dtype == RAZOR_F32) {
             *reinterpret_cast<float4 *>(static_cast<float *>(O) + (int64_t)bj * D + 4 * col) = num;
