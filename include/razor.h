@@ -1,7 +1,8 @@
 /*
  * razor.h -- C ABI of the RazorAttention hot path for AMD MI355X (gfx950).
  *
- * Two device operations and one host-only planner:
+ * Two device operations, one host-only planner (and razor_column_sums, a stand-in for the
+ * prefill epilogue that lets razor_compress skip the dropped rows):
  *
  *   razor_plan         Algorithm 1, steps 2-3 as integer arithmetic: which rows
  *                      every (sequence, KV head) keeps, and where they live.
@@ -148,13 +149,30 @@ RAZOR_API int razor_plan(const razor_params *p, const int32_t *seq_lens_host,
  * never read.  kept_idx_dev (int32[total_rows], nullable) receives the kept positions.
  * After the call the arena is self-contained: the caller may release K and V.
  * Means are accumulated in fp32 in a fixed order (bit-reproducible run to run).
+ * col_sums (float32 [batch, n_kv_heads, 2, head_dim], nullable): sums of K and of V over rows
+ * [0, seq_len) of every head, e.g. accumulated by the kernel that wrote K and V during prefill
+ * (or by razor_column_sums).  When given, the dropped rows are not read at all: Eq.(4) is
+ * evaluated as (col_sums - sum of the kept rows) / N_d, which roughly halves the traffic of
+ * this call.  The subtraction loses accuracy when N_d is tiny against the sequence length.
  */
 RAZOR_API int razor_compress(const razor_params *p, const void *K, const void *V,
                    int64_t stride_b, int64_t stride_h, int64_t stride_n,
                    const int32_t *seq_lens_host, const uint8_t *retrieval_mask_host,
                    void *arena, float *comp, razor_head_desc *desc_dev,
-                   int32_t *kept_idx_dev, void *workspace, size_t workspace_bytes,
-                   void *stream);
+                   int32_t *kept_idx_dev, const float *col_sums, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
+/*
+ * Column sums of K and V over rows [0, seq_len) of every (sequence, KV head): what a prefill
+ * kernel's epilogue can accumulate while it writes the cache.  col_sums: float32
+ * [batch, n_kv_heads, 2, head_dim] (K sums, then V sums), fixed summation order.  Of p only
+ * batch, n_kv_heads, head_dim, dtype and n_workers matter (the rest must still be valid).
+ * The workspace is the one razor_plan sizes.
+ */
+RAZOR_API int razor_column_sums(const razor_params *p, const void *K, const void *V,
+                      int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                      const int32_t *seq_lens_host, float *col_sums, void *workspace,
+                      size_t workspace_bytes, void *stream);
 
 /*
  * One decode step.  If k_new and v_new ([batch, n_kv_heads, head_dim]) are non-NULL the

@@ -88,6 +88,28 @@ def select(N: int, retrieval: bool, n_sink: int, window: int):
     return kept[:n].copy(), lo.value, hi.value
 
 
+def widen(t) -> np.ndarray:
+    """Stored fp32 / bf16 values as float64 (exact)."""
+    a = as_raw(t)
+    if a.dtype == np.uint16:
+        a = (a.astype(np.uint32) << 16).view(np.float32)
+    return a.astype(np.float64)
+
+
+def column_sums(K, V, seq_lens) -> np.ndarray:
+    """float64 [B, H, 2, d]: sums of the K rows and of the V rows over positions [0, seq_len).
+    Together with the sums over the kept rows this gives the numerator of Eq.(4) by
+    subtraction, since the dropped and the kept rows partition the sequence."""
+    Kd, Vd = widen(K), widen(V)
+    B, H, _, d = Kd.shape
+    out = np.zeros((B, H, 2, d))
+    for b in range(B):
+        n = int(seq_lens[b])
+        out[b, :, 0] = Kd[b, :, :n].sum(axis=1)
+        out[b, :, 1] = Vd[b, :, :n].sum(axis=1)
+    return out
+
+
 class OracleCache:
     """Compressed cache as the paper defines it, kept as (positions, khat, vhat, N_d).
 

@@ -1,7 +1,7 @@
 """Python binding of the razor C-ABI library (RazorAttention hot path on MI355X).
 
-The functions `razor_plan`, `razor_compress`, `razor_decode_attn`, `razor_profile_events`
-and `razor_strerror` carry the names and the argument order of `include/razor.h`; they only marshal
+The functions `razor_plan`, `razor_compress`, `razor_column_sums`, `razor_decode_attn`,
+`razor_profile_events` and `razor_strerror` carry the names and the argument order of `include/razor.h`; they only marshal
 arguments (torch tensors -> device pointers, numpy arrays -> host pointers).  Every
 step of the path runs in the HIP kernels of `librazor.so`; there is no Python or CPU
 fallback: a missing library raises on first use.
@@ -27,8 +27,8 @@ RAZOR_BLOCK_ROWS = 16
 RAZOR_MAX_GROUP = 16
 RAZOR_MAX_WORKERS = 8192
 
-EXPORTS = ("razor_plan", "razor_compress", "razor_decode_attn", "razor_profile_events",
-           "razor_strerror")
+EXPORTS = ("razor_plan", "razor_compress", "razor_column_sums", "razor_decode_attn",
+           "razor_profile_events", "razor_strerror")
 
 
 class RazorParams(ctypes.Structure):
@@ -84,7 +84,9 @@ def load_library():
     L.razor_plan.restype = ctypes.c_int
     L.razor_plan.argtypes = [PP, vp, vp, vp, vp, ctypes.POINTER(RazorSizes)]
     L.razor_compress.restype = ctypes.c_int
-    L.razor_compress.argtypes = [PP, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.razor_compress.argtypes = [PP, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.razor_column_sums.restype = ctypes.c_int
+    L.razor_column_sums.argtypes = [PP, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
     L.razor_decode_attn.restype = ctypes.c_int
     L.razor_decode_attn.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.razor_profile_events.restype = ctypes.c_int
@@ -124,12 +126,22 @@ def razor_plan(params: RazorParams, seq_lens_host: np.ndarray, retrieval_mask_ho
 
 def razor_compress(params: RazorParams, K, V, stride_b: int, stride_h: int, stride_n: int,
                    seq_lens_host: np.ndarray, retrieval_mask_host: np.ndarray, arena, comp,
-                   desc_dev, kept_idx_dev, workspace, workspace_bytes: int, stream: int = 0) -> int:
+                   desc_dev, kept_idx_dev, col_sums, workspace, workspace_bytes: int,
+                   stream: int = 0) -> int:
     assert seq_lens_host.dtype == np.int32 and retrieval_mask_host.dtype == np.uint8
     return load_library().razor_compress(
         ctypes.byref(params), _dev(K), _dev(V), stride_b, stride_h, stride_n,
         _host(seq_lens_host), _host(retrieval_mask_host), _dev(arena), _dev(comp), _dev(desc_dev),
-        _dev(kept_idx_dev), _dev(workspace), workspace_bytes, stream or None)
+        _dev(kept_idx_dev), _dev(col_sums), _dev(workspace), workspace_bytes, stream or None)
+
+
+def razor_column_sums(params: RazorParams, K, V, stride_b: int, stride_h: int, stride_n: int,
+                      seq_lens_host: np.ndarray, col_sums, workspace, workspace_bytes: int,
+                      stream: int = 0) -> int:
+    assert seq_lens_host.dtype == np.int32
+    return load_library().razor_column_sums(
+        ctypes.byref(params), _dev(K), _dev(V), stride_b, stride_h, stride_n, _host(seq_lens_host),
+        _dev(col_sums), _dev(workspace), workspace_bytes, stream or None)
 
 
 def razor_decode_attn(params: RazorParams, Q, k_new, v_new, arena, comp, desc_dev, O, workspace,
@@ -204,13 +216,27 @@ class RazorCache:
     def _stream(self) -> int:
         return self.torch.cuda.current_stream(self.device).cuda_stream
 
-    def compress(self, K, V) -> None:
-        """K, V: [B, H_kv, N, d] device tensors, last dimension contiguous."""
+    def _check_source(self, K, V) -> None:
         assert K.dtype == self.dtype and V.dtype == self.dtype and K.stride() == V.stride()
         assert K.stride(3) == 1 and K.shape[:2] == (self.params.batch, self.params.n_kv_heads)
         assert K.shape[2] >= int(self.seq_lens.max()) and K.shape[3] == self.params.head_dim
+
+    def column_sums(self, K, V):
+        """float32 [B, H_kv, 2, d]: sums of K and V over the valid rows (what a prefill epilogue gives)."""
+        self._check_source(K, V)
+        p = self.params
+        out = self.torch.empty(p.batch, p.n_kv_heads, 2, p.head_dim, dtype=self.torch.float32, device=self.device)
+        _check(razor_column_sums(p, K, V, K.stride(0), K.stride(1), K.stride(2), self.seq_lens, out,
+                                 self.workspace, self.workspace.numel(), self._stream()), "razor_column_sums")
+        return out
+
+    def compress(self, K, V, col_sums=None) -> None:
+        """K, V: [B, H_kv, N, d] device tensors, last dimension contiguous.  col_sums: optional
+        float32 [B, H_kv, 2, d] sums over the valid rows; with it the dropped rows are not read."""
+        self._check_source(K, V)
+        assert col_sums is None or (col_sums.dtype == self.torch.float32 and col_sums.is_contiguous())
         _check(razor_compress(self.params, K, V, K.stride(0), K.stride(1), K.stride(2), self.seq_lens,
-                              self.mask, self.arena, self.comp, self.desc_dev, self.kept_idx_dev,
+                              self.mask, self.arena, self.comp, self.desc_dev, self.kept_idx_dev, col_sums,
                               self.workspace, self.workspace.numel(), self._stream()), "razor_compress")
         self.n_appended = 0
 

@@ -56,12 +56,13 @@ __device__ __forceinline__ void accumulate_piece(const uint4 &v, float *acc)
     }
 }
 
-// Eq.(4), first level.  The dropped ranges of all heads form one axis of 16-row blocks, cut
-// into equal ranges, one per wavefront (same scheme as the decode kernel).  A wave streams
-// its rows once -- lane (prow, piece) owns one 16-byte piece of rows prow, prow + RPI, ... of
+// Eq.(4), first level.  The rows to be summed (ROWS: the dropped set of every head, or the
+// kept rows of the compressed heads, or every row) form one axis of 16-row blocks, cut into
+// equal ranges, one per wavefront (same scheme as the decode kernel).  A wave streams its
+// rows once -- lane (prow, piece) owns one 16-byte piece of rows prow, prow + RPI, ... of
 // every block -- keeps fp32 column sums of K and V, adds the row groups with shuffles and
 // stores one partial sum per head segment into slot wave + head.  Fixed order throughout.
-template <int DTYPE, int D>
+template <int DTYPE, int D, class ROWS>
 __global__ __launch_bounds__(256) void mean_stream_kernel(
     const char *__restrict__ K, const char *__restrict__ V, int64_t stride_b, int64_t stride_h,
     int64_t stride_n, const razor_head_desc *__restrict__ desc, int n_heads, int n_kv_heads,
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(256) void mean_stream_kernel(
     const int lane = threadIdx.x & 63;
     const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int prow = lane / LPR, piece = lane % LPR;
-    const DroppedBlocks count;
+    const RowSetBlocks<ROWS> count;
     int total, per, lo, hi, i, first;
     plan_range(count, desc, n_heads, n_workers, w, lane, total, per, lo, hi, i, first);
     if (w == 0) write_prefix(count, desc, n_heads, lane, per, prefix);
@@ -83,16 +84,16 @@ __global__ __launch_bounds__(256) void mean_stream_kernel(
 
     while (lo < hi) {
         razor_head_desc e = desc[i];
-        while (first + (e.n_dropped + kBlockRows - 1) / kBlockRows <= lo) {
-            first += (e.n_dropped + kBlockRows - 1) / kBlockRows;
+        while (first + (ROWS::n(e.rows, e.n_dropped) + kBlockRows - 1) / kBlockRows <= lo) {
+            first += (ROWS::n(e.rows, e.n_dropped) + kBlockRows - 1) / kBlockRows;
             e = desc[++i];
         }
-        const int head_end = first + (e.n_dropped + kBlockRows - 1) / kBlockRows;
+        const int n_rows = ROWS::n(e.rows, e.n_dropped);
+        const int head_end = first + (n_rows + kBlockRows - 1) / kBlockRows;
         const int seg_end = hi < head_end ? hi : head_end;
         const int b = i / n_kv_heads, h = i % n_kv_heads;
         const int64_t base = (b * stride_b + h * stride_h) * ES + piece * 16;
         const int64_t row_bytes = stride_n * ES;
-        const int d_lo = n_sink, d_hi = n_sink + e.n_dropped;
 
         float ak[NE], av[NE];
 #pragma unroll
@@ -101,9 +102,9 @@ __global__ __launch_bounds__(256) void mean_stream_kernel(
         auto load_block = [&](int t, uint4(&k)[NI], uint4(&v)[NI]) {
 #pragma unroll
             for (int r = 0; r < NI; ++r) {
-                int row = d_lo + t * kBlockRows + r * RPI + prow;
-                const bool valid = row < d_hi;
-                row = valid ? row : d_hi - 1;
+                const int idx = t * kBlockRows + r * RPI + prow;
+                const bool valid = idx < n_rows;
+                const int64_t row = ROWS::row(valid ? idx : n_rows - 1, e.rows, e.n_dropped, n_sink);
                 k[r] = stream_load16(K + base + row * row_bytes);
                 v[r] = stream_load16(V + base + row * row_bytes);
                 if (!valid) k[r] = v[r] = make_uint4(0, 0, 0, 0);   // +0.0 in either format
@@ -151,17 +152,24 @@ __global__ __launch_bounds__(256) void mean_stream_kernel(
 
 // Eq.(4), second level: add the segment sums of a head (four interleaved groups, each in
 // slot order, then the groups in order; double keeps the result independent of how the rows
-// were cut) and divide by N_d.  blockDim = (2 * D, 4).
-template <int D>
+// were cut).  blockDim = (2 * D, 4).
+//   kFinalMean        comp = sum / N_d                  (the streamed rows were the dropped set)
+//   kFinalComplement  comp = (col_sums - sum) / N_d     (the streamed rows were the kept ones and
+//                     col_sums holds the sums over the whole sequence)
+//   kFinalSum         comp = sum                        (plain column sums)
+enum { kFinalMean = 0, kFinalComplement = 1, kFinalSum = 2 };
+
+template <int D, int MODE, class ROWS>
 __global__ void mean_final_kernel(const razor_head_desc *__restrict__ desc, int n_heads,
                                   const int32_t *__restrict__ prefix,
-                                  const float *__restrict__ partial, float *__restrict__ comp)
+                                  const float *__restrict__ partial,
+                                  const float *__restrict__ col_sums, float *__restrict__ comp)
 {
     __shared__ double red[4][2 * D];
     const int head = blockIdx.x, t = threadIdx.x, grp = threadIdx.y;
-    const int n_dropped = desc[head].n_dropped;
+    const razor_head_desc e = desc[head];
     double s = 0.0;
-    if (n_dropped > 0) {
+    if (ROWS::n(e.rows, e.n_dropped) > 0) {
         const int first = prefix[head], last = prefix[head + 1], per = prefix[n_heads + 1];
         const int w0 = first / per, n_slots = (last - 1) / per - w0 + 1;
         for (int k = grp; k < n_slots; k += 4)
@@ -171,7 +179,12 @@ __global__ void mean_final_kernel(const razor_head_desc *__restrict__ desc, int 
     __syncthreads();
     if (grp == 0) {
         const double sum = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
-        comp[(size_t)head * 2 * D + t] = n_dropped > 0 ? (float)(sum / (double)n_dropped) : 0.f;
+        float out;
+        if (MODE == kFinalSum) out = (float)sum;
+        else if (e.n_dropped <= 0) out = 0.f;
+        else if (MODE == kFinalMean) out = (float)(sum / (double)e.n_dropped);
+        else out = (float)(((double)col_sums[(size_t)head * 2 * D + t] - sum) / (double)e.n_dropped);
+        comp[(size_t)head * 2 * D + t] = out;
     }
 }
 
@@ -256,8 +269,8 @@ template <int DTYPE, int D>
 int launch_compress(const razor_params &p, const char *K, const char *V, int64_t stride_b,
                     int64_t stride_h, int64_t stride_n, const std::vector<razor_head_desc> &desc,
                     int max_dropped, char *arena, float *comp, razor_head_desc *desc_dev,
-                    int32_t *kept_idx_dev, int32_t *prefix, float *partial, int workers,
-                    hipStream_t stream)
+                    int32_t *kept_idx_dev, const float *col_sums, int32_t *prefix, float *partial,
+                    int workers, hipStream_t stream)
 {
     constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
     const int n_heads = (int)desc.size();
@@ -272,12 +285,25 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
     int max_rows = 0;
     for (const razor_head_desc &e : desc) max_rows = std::max(max_rows, e.rows);
     const dim3 grid((workers + 3) / 4);
-    if (max_dropped > 0)
-        hipLaunchKernelGGL((mean_stream_kernel<DTYPE, D>), grid, dim3(256), 0, stream, K, V, stride_b,
-                           stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads, p.n_sink, workers,
-                           prefix, partial);
-    hipLaunchKernelGGL((mean_final_kernel<D>), dim3(n_heads), dim3(2 * D, 4), 0, stream, desc_dev,
-                       n_heads, prefix, partial, comp);
+    if (max_dropped > 0 && !col_sums) {
+        // Eq.(4) as it stands: stream the dropped rows
+        hipLaunchKernelGGL((mean_stream_kernel<DTYPE, D, DroppedRows>), grid, dim3(256), 0, stream, K, V,
+                           stride_b, stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads, p.n_sink,
+                           workers, prefix, partial);
+        hipLaunchKernelGGL((mean_final_kernel<D, kFinalMean, DroppedRows>), dim3(n_heads), dim3(2 * D, 4), 0,
+                           stream, desc_dev, n_heads, prefix, partial, col_sums, comp);
+    } else if (max_dropped > 0) {
+        // the caller already holds the column sums over the whole sequence (a prefill epilogue can
+        // accumulate them for free): stream only the few kept rows and take the complement
+        hipLaunchKernelGGL((mean_stream_kernel<DTYPE, D, KeptRowsOfCompressedHeads>), grid, dim3(256), 0,
+                           stream, K, V, stride_b, stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads,
+                           p.n_sink, workers, prefix, partial);
+        hipLaunchKernelGGL((mean_final_kernel<D, kFinalComplement, KeptRowsOfCompressedHeads>), dim3(n_heads),
+                           dim3(2 * D, 4), 0, stream, desc_dev, n_heads, prefix, partial, col_sums, comp);
+    } else {
+        hipLaunchKernelGGL((mean_final_kernel<D, kFinalMean, DroppedRows>), dim3(n_heads), dim3(2 * D, 4), 0,
+                           stream, desc_dev, n_heads, prefix, partial, col_sums, comp);
+    }
     if (max_rows > 0) {
         const int groups = ((max_rows + kBlockRows - 1) / kBlockRows + 3) / 4;
         hipLaunchKernelGGL((compact_kernel<D * ES>), dim3(groups, n_heads), dim3(256), 0, stream, K, V,
@@ -293,25 +319,98 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
     return RAZOR_OK;
 }
 
+template <int DTYPE, int D>
+int launch_column_sums(const razor_params &p, const char *K, const char *V, int64_t stride_b,
+                       int64_t stride_h, int64_t stride_n, const std::vector<razor_head_desc> &desc,
+                       razor_head_desc *desc_dev, float *sums, int32_t *prefix, float *partial,
+                       int workers, hipStream_t stream)
+{
+    const int n_heads = (int)desc.size();
+    for (int first = 0; first < n_heads; first += kDescPerLaunch) {
+        DescBatch batch;
+        const int count = std::min(kDescPerLaunch, n_heads - first);
+        for (int i = 0; i < count; ++i) batch.d[i] = desc[(size_t)first + i];
+        for (int i = count; i < kDescPerLaunch; ++i) batch.d[i] = razor_head_desc{};
+        hipLaunchKernelGGL(upload_desc_kernel, dim3(1), dim3(kDescPerLaunch), 0, stream, batch,
+                           first, count, desc_dev);
+    }
+    hipLaunchKernelGGL((mean_stream_kernel<DTYPE, D, AllRows>), dim3((workers + 3) / 4), dim3(256), 0,
+                       stream, K, V, stride_b, stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads,
+                       p.n_sink, workers, prefix, partial);
+    hipLaunchKernelGGL((mean_final_kernel<D, kFinalSum, AllRows>), dim3(n_heads), dim3(2 * D, 4), 0, stream,
+                       desc_dev, n_heads, prefix, partial, nullptr, sums);
+    RAZOR_HIP_CHECK(hipGetLastError());
+    return RAZOR_OK;
+}
+
+// Shared argument checks of the two entry points that read the full cache.
+int check_source(const razor_params *p, const void *K, const void *V, int64_t stride_b,
+                 int64_t stride_h, int64_t stride_n)
+{
+    if (check_params(p) != RAZOR_OK) return RAZOR_EINVAL;
+    if (!K || !V) return RAZOR_EINVAL;
+    const int64_t align = 16 / elem_size(p->dtype);   // rows must start on 16-byte boundaries
+    if (stride_n < p->head_dim || stride_n % align || stride_h % align || stride_b % align)
+        return RAZOR_EINVAL;
+    if (stride_b < 0 || stride_h < 0) return RAZOR_EINVAL;
+    if (((uintptr_t)K | (uintptr_t)V) & 15) return RAZOR_EINVAL;
+    return RAZOR_OK;
+}
+
 }  // namespace
 }  // namespace razor
+
+extern "C" int razor_column_sums(const razor_params *p, const void *K, const void *V,
+                                 int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                                 const int32_t *seq_lens_host, float *col_sums, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    using namespace razor;
+    if (check_source(p, K, V, stride_b, stride_h, stride_n) != RAZOR_OK) return RAZOR_EINVAL;
+    if (!seq_lens_host || !col_sums || ((uintptr_t)col_sums & 15)) return RAZOR_EINVAL;
+    // every head keeps everything: rows = seq_len, which is all AllRows needs from the table
+    std::vector<uint8_t> all(p->n_kv_heads, 1);
+    std::vector<razor_head_desc> desc;
+    razor_sizes sizes;
+    int max_dropped = 0;
+    int rc = build_plan(*p, seq_lens_host, all.data(), desc, sizes, max_dropped);
+    if (rc != RAZOR_OK) return rc;
+    const CompressWorkspace ws = compress_workspace(*p);
+    if (!workspace || workspace_bytes < ws.bytes) return RAZOR_ECAPACITY;
+    int workers = p->n_workers;
+    if (workers == 0) {
+        rc = auto_workers(&workers);
+        if (rc != RAZOR_OK) return rc;
+    }
+    workers = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
+    char *wsb = static_cast<char *>(workspace);
+    int32_t *prefix = reinterpret_cast<int32_t *>(wsb + ws.prefix_off);
+    float *partial = reinterpret_cast<float *>(wsb + ws.partial_off);
+    razor_head_desc *desc_dev = reinterpret_cast<razor_head_desc *>(wsb + ws.desc_off);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const char *k = static_cast<const char *>(K), *v = static_cast<const char *>(V);
+#define RAZOR_DISPATCH(DT, DD)                                                                      \
+    return launch_column_sums<DT, DD>(*p, k, v, stride_b, stride_h, stride_n, desc, desc_dev,       \
+                                      col_sums, prefix, partial, workers, s)
+    if (p->dtype == RAZOR_BF16 && p->head_dim == 128) RAZOR_DISPATCH(RAZOR_BF16, 128);
+    if (p->dtype == RAZOR_BF16 && p->head_dim == 64) RAZOR_DISPATCH(RAZOR_BF16, 64);
+    if (p->dtype == RAZOR_F32 && p->head_dim == 128) RAZOR_DISPATCH(RAZOR_F32, 128);
+    if (p->dtype == RAZOR_F32 && p->head_dim == 64) RAZOR_DISPATCH(RAZOR_F32, 64);
+#undef RAZOR_DISPATCH
+    return RAZOR_EINVAL;
+}
 
 extern "C" int razor_compress(const razor_params *p, const void *K, const void *V,
                               int64_t stride_b, int64_t stride_h, int64_t stride_n,
                               const int32_t *seq_lens_host, const uint8_t *retrieval_mask_host,
                               void *arena, float *comp, razor_head_desc *desc_dev,
-                              int32_t *kept_idx_dev, void *workspace, size_t workspace_bytes,
-                              void *stream)
+                              int32_t *kept_idx_dev, const float *col_sums, void *workspace,
+                              size_t workspace_bytes, void *stream)
 {
     using namespace razor;
-    if (check_params(p) != RAZOR_OK) return RAZOR_EINVAL;
-    if (!K || !V || !seq_lens_host || !retrieval_mask_host || !comp || !desc_dev) return RAZOR_EINVAL;
-    const int es = elem_size(p->dtype);
-    const int64_t align = 16 / es;   // rows must start on 16-byte boundaries
-    if (stride_n < p->head_dim || stride_n % align || stride_h % align || stride_b % align)
-        return RAZOR_EINVAL;
-    if (stride_b < 0 || stride_h < 0) return RAZOR_EINVAL;
-    if (((uintptr_t)K | (uintptr_t)V | (uintptr_t)arena | (uintptr_t)comp) & 15) return RAZOR_EINVAL;
+    if (check_source(p, K, V, stride_b, stride_h, stride_n) != RAZOR_OK) return RAZOR_EINVAL;
+    if (!seq_lens_host || !retrieval_mask_host || !comp || !desc_dev) return RAZOR_EINVAL;
+    if (((uintptr_t)arena | (uintptr_t)comp | (uintptr_t)col_sums) & 15) return RAZOR_EINVAL;
 
     std::vector<razor_head_desc> desc;
     razor_sizes sizes;
@@ -335,7 +434,7 @@ extern "C" int razor_compress(const razor_params *p, const void *K, const void *
     workers = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
 #define RAZOR_DISPATCH(DT, DD)                                                                    \
     return launch_compress<DT, DD>(*p, k, v, stride_b, stride_h, stride_n, desc, max_dropped, a,  \
-                                   comp, desc_dev, kept_idx_dev, prefix, partial, workers, s)
+                                   comp, desc_dev, kept_idx_dev, col_sums, prefix, partial, workers, s)
     if (p->dtype == RAZOR_BF16 && p->head_dim == 128) RAZOR_DISPATCH(RAZOR_BF16, 128);
     if (p->dtype == RAZOR_BF16 && p->head_dim == 64) RAZOR_DISPATCH(RAZOR_BF16, 64);
     if (p->dtype == RAZOR_F32 && p->head_dim == 128) RAZOR_DISPATCH(RAZOR_F32, 128);

@@ -71,11 +71,29 @@ struct CachedBlocks {   // rows held this decode step (the token being appended 
         return f.z + (slides(f.x, (uint32_t)f.w, window) ? 1 : 0);
     }
 };
-struct DroppedBlocks {  // rows Eq.(4) averages
+// Row sets a streaming column sum can run over: n(e) source rows per head, the t-th of which is
+// source row row(t, e, n_sink).
+struct DroppedRows {      // the set D of Eq.(4)
+    static __device__ __forceinline__ int n(int rows, int n_dropped) { return n_dropped; }
+    static __device__ __forceinline__ int64_t row(int t, int rows, int n_dropped, int n_sink) { return (int64_t)n_sink + t; }
+};
+struct KeptRowsOfCompressedHeads {   // sinks + window of the heads that dropped rows
+    static __device__ __forceinline__ int n(int rows, int n_dropped) { return n_dropped > 0 ? rows : 0; }
+    static __device__ __forceinline__ int64_t row(int t, int rows, int n_dropped, int n_sink)
+    {
+        return t < n_sink ? (int64_t)t : (int64_t)t + n_dropped;
+    }
+};
+struct AllRows {          // every valid row of the sequence
+    static __device__ __forceinline__ int n(int rows, int n_dropped) { return rows + n_dropped; }
+    static __device__ __forceinline__ int64_t row(int t, int rows, int n_dropped, int n_sink) { return t; }
+};
+template <class ROWS>
+struct RowSetBlocks {     // 16-row blocks of such a set
     __device__ __forceinline__ int operator()(const razor_head_desc *__restrict__ desc, int idx) const
     {
-        const int nd = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(desc + idx) + 24);
-        return (nd + kBlockRows - 1) / kBlockRows;
+        const int4 f = *reinterpret_cast<const int4 *>(reinterpret_cast<const char *>(desc + idx) + 16);
+        return (ROWS::n(f.x, f.z) + kBlockRows - 1) / kBlockRows;   // {rows, cap, n_dropped, flags}
     }
 };
 

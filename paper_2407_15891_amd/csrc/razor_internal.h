@@ -31,6 +31,7 @@ DecodeWorkspace decode_workspace(const razor_params &p);
 struct CompressWorkspace {
     size_t prefix_off;   // int32[n_heads + 2]: dropped-block prefix sums, then blocks-per-worker
     size_t partial_off;  // float[slots][2][head_dim]: column sums per (worker, head) segment
+    size_t desc_off;     // razor_head_desc[n_heads]: private table of razor_column_sums
     size_t bytes;
 };
 CompressWorkspace compress_workspace(const razor_params &p);

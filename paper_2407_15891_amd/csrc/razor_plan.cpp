@@ -63,7 +63,8 @@ CompressWorkspace compress_workspace(const razor_params &p)
     CompressWorkspace w;
     w.prefix_off = 0;
     w.partial_off = round_up((n_heads + 2) * sizeof(int32_t), 256);
-    w.bytes = w.partial_off + (RAZOR_MAX_WORKERS + n_heads) * 2 * p.head_dim * sizeof(float);
+    w.desc_off = w.partial_off + (RAZOR_MAX_WORKERS + n_heads) * 2 * p.head_dim * sizeof(float);
+    w.bytes = w.desc_off + round_up(n_heads * sizeof(razor_head_desc), 256);
     return w;
 }
 

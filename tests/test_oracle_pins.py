@@ -362,6 +362,36 @@ def test_widening_is_exact():
 
 
 # ----------------------------------------------------------------- planted mistakes are caught
+def test_column_sums_closed_form_and_partition_identity():
+    """Rows n of a head hold the value n (+ column c for V): Gauss's sum pins the routine; then
+    Eq.(4)'s mean equals (all rows - kept rows) / N_d because D and the kept set partition [0, N)."""
+    B, H, N, d = 2, 3, 301, 64
+    n = np.arange(N, dtype=np.float32)
+    K = np.broadcast_to(n[None, None, :, None], (B, H, N, d)).copy()
+    V = K + np.arange(d, dtype=np.float32)
+    seq = np.array([301, 120], np.int32)
+    cs = orc.column_sums(K, V, seq)
+    for b, L in enumerate(seq):
+        L = int(L)
+        assert (cs[b, :, 0] == L * (L - 1) / 2).all()
+        np.testing.assert_array_equal(cs[b, :, 1], L * (L - 1) / 2 + L * np.arange(d)[None, :].repeat(H, 0))
+    rng = np.random.default_rng(5)
+    K = rng.standard_normal((B, H, N, d)).astype(np.float32)
+    V = rng.standard_normal((B, H, N, d)).astype(np.float32)
+    mask = np.array([0, 1, 0], np.uint8)
+    oc = orc.OracleCache(K, V, seq, mask, 4, 50)
+    cs = orc.column_sums(K, V, seq)
+    for b in range(B):
+        for h in range(H):
+            if oc.N_d[b, h] == 0:
+                continue
+            kept = oc.kept_of(b, h)
+            np.testing.assert_allclose((cs[b, h, 0] - K[b, h][kept].astype(np.float64).sum(0)) / oc.N_d[b, h],
+                                       oc.khat[b, h], rtol=0, atol=1e-12)
+            np.testing.assert_allclose((cs[b, h, 1] - V[b, h][kept].astype(np.float64).sum(0)) / oc.N_d[b, h],
+                                       oc.vhat[b, h], rtol=0, atol=1e-12)
+
+
 def test_pins_catch_planted_mistakes():
     """A dropped N_d factor, a missing ln N_d in the shift, or means taken over the wrong
     range all change the brute-force value by far more than the pin tolerances."""

@@ -61,7 +61,7 @@ def make_pair(w, **kw):
     return cache, oc
 
 
-def check_compress(w, cache, oc, what):
+def check_compress(w, cache, oc, what, comp_atol=4e-6):
     desc = cache.desc()
     kept_dev = cache.kept_idx_dev.cpu().numpy()
     comp = cache.comp.cpu().numpy().reshape(w.B, w.Hkv, 2, w.d).astype(np.float64)
@@ -78,8 +78,8 @@ def check_compress(w, cache, oc, what):
             k, v = arena_rows(cache, desc, i)
             np.testing.assert_array_equal(k, Kb[b, h][kept], err_msg=f"{what} K rows head {i}")
             np.testing.assert_array_equal(v, Vb[b, h][kept], err_msg=f"{what} V rows head {i}")
-            np.testing.assert_allclose(comp[b, h, 0], oc.khat[b, h], rtol=0, atol=4e-6 * scale_in, err_msg=what)
-            np.testing.assert_allclose(comp[b, h, 1], oc.vhat[b, h], rtol=0, atol=4e-6 * scale_in, err_msg=what)
+            np.testing.assert_allclose(comp[b, h, 0], oc.khat[b, h], rtol=0, atol=comp_atol * scale_in, err_msg=what)
+            np.testing.assert_allclose(comp[b, h, 1], oc.vhat[b, h], rtol=0, atol=comp_atol * scale_in, err_msg=what)
 
 
 def run_steps(w, cache, oc, steps, what, append=True, use_comp=True, bf16_out=False):
@@ -110,6 +110,33 @@ def test_compress_parity(cfg, context, window, batch):
     check_compress(w, cache, oc, f"cfg{cfg}")
 
 
+@pytest.mark.parametrize("cfg,context,window,batch", [
+    (1, 2048, 256, 1),
+    (1, 1000, 100, 3),
+    (3, 5000, 700, 2),
+    (4, 6000, 333, 5),        # ragged sequence lengths
+])
+def test_compress_from_column_sums(cfg, context, window, batch):
+    """Eq.(4) by subtraction: sums over all rows (the stand-in for a prefill epilogue) minus the
+    kept rows.  The sums carry fp32 rounding of a value up to seq_len * max|x|, divided by N_d:
+    a few 1e-7 * seq_len / N_d relative to max|x|, bounded here by 2e-5."""
+    say(f"compress from column sums cfg={cfg} context={context} window={window} batch={batch}")
+    w = make_workload(cfg, DEV, context=context, window=window, batch=batch, max_new=3)
+    cache = razor.RazorCache.from_workload(w, want_kept_idx=True)
+    sums = cache.column_sums(w.K, w.V)
+    ref = orc.column_sums(w.K.cpu(), w.V.cpu(), w.seq_lens)
+    scale_in = float(w.K.abs().max())
+    tol = 2e-7 * scale_in * np.asarray(w.seq_lens, np.float64)[:, None, None, None]
+    assert (np.abs(sums.cpu().numpy().astype(np.float64) - ref) <= tol).all()
+    cache.compress(w.K, w.V, col_sums=sums)
+    oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, w.n_sink, w.window, max_new=3)
+    check_compress(w, cache, oc, f"cfg{cfg} column sums", comp_atol=2e-5)
+    run_steps(w, cache, oc, 2, f"cfg{cfg} column sums")
+    # same bits on a second run (fixed summation order)
+    again = cache.column_sums(w.K, w.V)
+    assert torch.equal(again, sums)
+
+
 def test_compress_strided_input_and_fp32_dim128():
     say("compress parity: strided K/V views, fp32 head_dim 128, bf16 head_dim 64")
     for dtype, d in ((torch.float32, 128), (torch.bfloat16, 64), (torch.float32, 64), (torch.bfloat16, 128)):
@@ -128,6 +155,8 @@ def test_compress_strided_input_and_fp32_dim128():
             pass
         w = W(); w.B, w.Hkv, w.d, w.K, w.V = 2, 3, d, K.contiguous(), V.contiguous()
         check_compress(w, cache, oc, f"strided {dtype} d={d}")
+        cache.compress(K, V, col_sums=cache.column_sums(K, V))
+        check_compress(w, cache, oc, f"strided {dtype} d={d} column sums", comp_atol=2e-5)
         # and the cache answers queries correctly
         Q = torch.randn(2, 6, d, generator=g, device=DEV).to(dtype)
         check_output(cache.decode(Q), oc.decode(Q.cpu(), d ** -0.5), f"strided {dtype} d={d}")

@@ -123,15 +123,18 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     fake = 4096   # never dereferenced: validation fails first
     # null tensors
     assert L.razor_compress(pp, None, fake, 1, 1, 128, seq.ctypes.data, mask.ctypes.data, fake, fake,
-                            fake, None, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+                            fake, None, None, fake, 1 << 30, None) == razor.RAZOR_EINVAL
     # row stride shorter than a row / misaligned stride / misaligned pointer
     for strides, k in (((100 * 64, 64, 64), fake), ((100 * 132, 132 * 100, 132), fake),
                        ((100 * 128 * 4, 100 * 128, 128), fake + 2)):
         assert L.razor_compress(pp, k, fake, *strides, seq.ctypes.data, mask.ctypes.data, fake, fake,
-                                fake, None, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+                                fake, None, None, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+        assert L.razor_column_sums(pp, k, fake, *strides, seq.ctypes.data, fake, fake, 1 << 30, None) == razor.RAZOR_EINVAL
     # workspace too small
     assert L.razor_compress(pp, fake, fake, 4 * 100 * 128, 100 * 128, 128, seq.ctypes.data,
-                            mask.ctypes.data, fake, fake, fake, None, fake, 16, None) == razor.RAZOR_ECAPACITY
+                            mask.ctypes.data, fake, fake, fake, None, None, fake, 16, None) == razor.RAZOR_ECAPACITY
+    assert L.razor_column_sums(pp, fake, fake, 4 * 100 * 128, 100 * 128, 128, seq.ctypes.data, fake, fake, 16,
+                               None) == razor.RAZOR_ECAPACITY
     assert L.razor_decode_attn(pp, fake, None, None, fake, fake, fake, fake, fake, 16, None) == razor.RAZOR_ECAPACITY
     assert L.razor_decode_attn(pp, None, None, None, fake, fake, fake, fake, fake, 1 << 30, None) == razor.RAZOR_EINVAL
     # k_new without v_new
