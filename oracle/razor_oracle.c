@@ -11,6 +11,7 @@
  *   oracle_comp_token2  Eq.(4) over a dropped set that reaches into the appended rows
  *   oracle_attn_head    Eq.(5): attention over kept rows + compensation token
  *   oracle_decode_batch Algorithm 1, step 5: per-head dispatch over a batch
+ *   oracle_head_scores  Sec. 3.3: echo and induction score of every head on a repeated prompt
  *
  * No tiling, no online softmax, no fusion: two passes over the logits and
  * straight sums, so every line can be held against the paper by eye.
@@ -292,4 +293,59 @@ int oracle_compress_batch(const void *K, const void *V, int dtype,
     free(d_lo);
     free(d_hi);
     return n_threads;
+}
+
+/*
+ * Sec. 3.3 (identification of retrieval heads): the prompt is `period` random tokens
+ * repeated several times, n_tokens in all.  For a query position m >= period the echo
+ * token is the previous copy of the current token, position m - period, and the
+ * induction token is the one right after it, position m - period + 1.  A head's echo
+ * (induction) score is its causal softmax attention weight on that position, averaged
+ * over the positions m in [period, n_tokens) (earlier positions have no previous copy).
+ * With all_copies != 0 the weight is summed over every previous copy, m - j * period
+ * (+1), j = 1, 2, ... while that position is not negative.
+ *
+ * Q [n_q_heads, n_tokens, d], K [n_kv_heads, n_tokens, d] contiguous, after the rotary
+ * transformation; query head h reads KV head h / (n_q_heads / n_kv_heads).
+ * Every row of the attention map is formed in full: logits, maximum, sum, division.
+ */
+int oracle_head_scores(const void *Q, const void *K, int dtype, int n_q_heads, int n_kv_heads,
+                       int64_t n_tokens, int d, double scale, int64_t period, int all_copies,
+                       double *echo, double *induction)
+{
+    if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads || period < 1 || period >= n_tokens)
+        return -1;
+    const int g = n_q_heads / n_kv_heads;
+#pragma omp parallel for schedule(dynamic)
+    for (int h = 0; h < n_q_heads; ++h) {
+        double *w = (double *)malloc(sizeof(double) * (size_t)n_tokens);
+        double *q = (double *)malloc(sizeof(double) * (size_t)d);
+        double sum_echo = 0.0, sum_ind = 0.0;
+        for (int64_t m = period; m < n_tokens; ++m) {
+            for (int c = 0; c < d; ++c) q[c] = widen(Q, dtype, ((int64_t)h * n_tokens + m) * d + c);
+            double top = -INFINITY;
+            for (int64_t n = 0; n <= m; ++n) {                 /* causal: keys 0..m */
+                double dot = 0.0;
+                for (int c = 0; c < d; ++c)
+                    dot += q[c] * widen(K, dtype, ((int64_t)(h / g) * n_tokens + n) * d + c);
+                w[n] = scale * dot;
+                if (w[n] > top) top = w[n];
+            }
+            double denom = 0.0;
+            for (int64_t n = 0; n <= m; ++n) {
+                w[n] = exp(w[n] - top);
+                denom += w[n];
+            }
+            for (int64_t prev = m - period; prev >= 0; prev -= period) {
+                sum_echo += w[prev] / denom;
+                sum_ind += w[prev + 1] / denom;                /* prev + 1 <= m since period >= 1 */
+                if (!all_copies) break;
+            }
+        }
+        echo[h] = sum_echo / (double)(n_tokens - period);
+        induction[h] = sum_ind / (double)(n_tokens - period);
+        free(w);
+        free(q);
+    }
+    return 0;
 }

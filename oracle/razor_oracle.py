@@ -53,6 +53,8 @@ def lib():
         L.oracle_compress_batch.restype = ci
         L.oracle_compress_batch.argtypes = [vp, vp, ci, ci, ci, ci, i64, i64, i64,
                                             vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
+        L.oracle_head_scores.restype = ci
+        L.oracle_head_scores.argtypes = [vp, vp, ci, ci, ci, i64, ci, dbl, i64, ci, vp, vp]
         _lib = L
     return _lib
 
@@ -108,6 +110,41 @@ def column_sums(K, V, seq_lens) -> np.ndarray:
         out[b, :, 0] = Kd[b, :, :n].sum(axis=1)
         out[b, :, 1] = Vd[b, :, :n].sum(axis=1)
     return out
+
+
+def head_scores(Q, K, scale: float, period: int, all_copies: bool = False):
+    """Sec. 3.3: (echo, induction) score of every query head, float64 [n_q_heads] each.
+    Q [Hq, N, d], K [Hkv, N, d] (after the rotary transformation) for a prompt of `period`
+    random tokens repeated to N tokens."""
+    q, k = np.ascontiguousarray(as_raw(Q)), np.ascontiguousarray(as_raw(K))
+    Hq, N, d = q.shape
+    Hkv = k.shape[0]
+    assert k.shape == (Hkv, N, d) and q.dtype == k.dtype
+    echo, ind = np.zeros(Hq), np.zeros(Hq)
+    rc = lib().oracle_head_scores(_ptr(q), _ptr(k), _dtype_code(q), Hq, Hkv, N, d, float(scale), int(period),
+                                  int(bool(all_copies)), _ptr(echo), _ptr(ind))
+    assert rc == 0, "oracle_head_scores: bad arguments"
+    return echo, ind
+
+
+def protected_count(n_heads: int, frac: float) -> int:
+    """How many heads "top frac" of n_heads means: the nearest whole number, halves up."""
+    return int(np.floor(frac * n_heads + 0.5))
+
+
+def select_heads(echo, induction, group: int, frac_induction: float = 0.14, frac_echo: float = 0.01) -> np.ndarray:
+    """Sec. 3.3 / Table 2: retrieval heads = the top frac_induction of all heads by induction score
+    together with the top frac_echo by echo score (equal scores: the lower head index first).
+    Sec. 4.1 (grouped-query models): a KV head is retrieval when any query head of its group is.
+    Returns uint8 [n_heads / group]."""
+    echo, induction = np.asarray(echo, np.float64), np.asarray(induction, np.float64)
+    n = len(echo)
+    assert len(induction) == n and n % group == 0
+    chosen = np.zeros(n, bool)
+    for score, frac in ((induction, frac_induction), (echo, frac_echo)):
+        order = sorted(range(n), key=lambda i: (-score[i], i))
+        chosen[order[:protected_count(n, frac)]] = True
+    return chosen.reshape(n // group, group).any(axis=1).astype(np.uint8)
 
 
 class OracleCache:

@@ -144,3 +144,66 @@ def make_workload(cfg: int, device="cpu", *, context: Optional[int] = None,
                 t[:, h, :, ch] *= 8
     w.K, w.V = K, V
     return w
+
+
+# ----------------------------------------------------------------------------------------------
+# Inputs of the head-scoring pass (Sec. 3.3): one prompt of `period` random tokens repeated.
+
+@dataclass
+class ScoringWorkload:
+    Hq: int
+    Hkv: int
+    d: int
+    N: int                      # tokens in the prompt
+    period: int                 # tokens before the prompt repeats
+    scale: float
+    Q: torch.Tensor             # [Hq, N, d], as after the rotary transformation
+    K: torch.Tensor             # [Hkv, N, d]
+    tokens: np.ndarray          # int64 [N]
+    echo_kv: np.ndarray         # KV heads built to look back at the previous copy of the current token
+    induction_kv: np.ndarray    # KV heads built to look at the token after that copy
+
+
+def make_scoring_workload(device="cpu", *, n_q_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
+                          period: int = 2500, n_tokens: Optional[int] = None, n_echo_kv: int = 1,
+                          n_induction_kv: int = 1, seed: int = 0,
+                          dtype: torch.dtype = torch.bfloat16) -> ScoringWorkload:
+    """The paper feeds a trained model 2500 random tokens repeated 4 times and reads its attention
+    maps.  There are no weights here, so Q and K are drawn directly with the structure that makes
+    such a prompt informative: every token id has a random unit embedding; a query carries the
+    embedding of its own token; the keys of an "echo" KV head carry the embedding of their own
+    token, those of an "induction" KV head the embedding of the token before them, all other KV
+    heads only noise.  Every key head also has one large first key (a sink) along a direction all
+    queries share.  Query heads of one group differ in how strongly they carry the token embedding,
+    so scores vary inside a group."""
+    N = 4 * period if n_tokens is None else n_tokens
+    assert n_q_heads % n_kv_heads == 0 and n_echo_kv + n_induction_kv <= n_kv_heads and 1 <= period < N
+    dev = torch.device(device)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(977 * seed + 31)
+    first = torch.randint(0, 50000, (period,), generator=g)
+    tokens = first.repeat((N + period - 1) // period)[:N]
+    ids = torch.unique(tokens, return_inverse=True)[1]                     # dense ids of the tokens used
+    emb = torch.randn(int(ids.max()) + 1, head_dim, generator=g)
+    emb = emb / emb.norm(dim=1, keepdim=True)
+    own = emb[ids]                                                         # [N, d]
+    before = torch.cat([torch.zeros(1, head_dim), own[:-1]])               # embedding of the previous token
+    sink_dir = torch.randn(head_dim, generator=g)
+    sink_dir = sink_dir / sink_dir.norm()
+    kinds = torch.randperm(n_kv_heads, generator=g)
+    echo_kv = np.sort(kinds[:n_echo_kv].numpy())
+    induction_kv = np.sort(kinds[n_echo_kv:n_echo_kv + n_induction_kv].numpy())
+    gain = float(head_dim) ** 0.5
+    K = 0.5 * torch.randn(n_kv_heads, N, head_dim, generator=g)
+    for j in echo_kv:
+        K[j] += gain * own
+    for j in induction_kv:
+        K[j] += gain * before
+    K[:, 0] += 4.0 * gain * sink_dir
+    strength = 0.3 + 0.7 * torch.rand(n_q_heads, generator=g)               # per query head
+    Q = 0.5 * torch.randn(n_q_heads, N, head_dim, generator=g)
+    Q += gain * strength[:, None, None] * own[None]
+    Q += 0.25 * gain * sink_dir
+    return ScoringWorkload(Hq=n_q_heads, Hkv=n_kv_heads, d=head_dim, N=N, period=period,
+                           scale=float(head_dim) ** -0.5, Q=Q.to(dtype).to(dev), K=K.to(dtype).to(dev),
+                           tokens=tokens.numpy(), echo_kv=echo_kv, induction_kv=induction_kv)
