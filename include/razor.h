@@ -191,6 +191,48 @@ RAZOR_API int razor_decode_attn(const razor_params *p, const void *Q, const void
                       size_t workspace_bytes, void *stream);
 
 /*
+ * Sec. 3.3, identification of retrieval heads: echo and induction score of every query head
+ * on a prompt made of `period` random tokens repeated up to n_tokens (the paper: 2500 tokens,
+ * four times).  For a query position m >= period the echo token is the previous copy of the
+ * current token, position m - period; the induction token follows it, position m - period + 1.
+ *   echo[h]      = mean over m in [period, n_tokens) of A_h[m, m - period]
+ *   induction[h] = mean over m in [period, n_tokens) of A_h[m, m - period + 1]
+ * with A_h the causal softmax(scale * Q_h K_h^T) attention map (query head h reads KV head
+ * h / (n_q_heads / n_kv_heads)).  all_copies != 0 sums the weight over every previous copy,
+ * m - j * period (+ 1), j = 1, 2, ..., instead of the nearest one.  The map is never stored.
+ *
+ * Q  device, [n_q_heads, n_tokens, head_dim] with element strides q_stride_h, q_stride_n, last
+ *    dimension contiguous, values as after the rotary transformation; K likewise
+ *    [n_kv_heads, n_tokens, head_dim].  Layers may be stacked along the head dimension.
+ *    dtype must be RAZOR_BF16 (matrix-core kernel), head_dim 64 or 128, strides multiples of 8
+ *    elements, base pointers 16-byte aligned, scale > 0, 1 <= period < n_tokens,
+ *    n_q_heads <= 65535.
+ * echo, induction  device, float32 [n_q_heads], written.
+ * workspace        device, at least razor_head_scores_workspace(n_q_heads, n_tokens) bytes
+ *                  (returns 0 for non-positive arguments); RAZOR_ECAPACITY if smaller.
+ * Everything is enqueued on `stream`; sums are taken in a fixed order (bit-reproducible).
+ */
+RAZOR_API size_t razor_head_scores_workspace(int n_q_heads, int n_tokens);
+RAZOR_API int razor_head_scores(const void *Q, const void *K, int dtype, int n_q_heads,
+                      int n_kv_heads, int head_dim, int n_tokens, int64_t q_stride_h,
+                      int64_t q_stride_n, int64_t k_stride_h, int64_t k_stride_n, float scale,
+                      int period, int all_copies, float *echo, float *induction,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Sec. 3.3 / Table 2 / Sec. 4.1, host only: turn scores into the retrieval mask razor_plan
+ * takes.  Of the n_heads query heads (all layers of the model, layer-major) the
+ * round(frac_induction * n_heads) with the highest induction score and the
+ * round(frac_echo * n_heads) with the highest echo score are retrieval heads (halves round up;
+ * equal scores: lower index first; the paper uses 0.14 and 0.01).  mask_host
+ * (uint8 [n_heads / group]) gets 1 for a KV head when any of its `group` query heads was
+ * chosen.  RAZOR_EINVAL for NaN scores, fractions outside [0, 1] or n_heads % group != 0.
+ */
+RAZOR_API int razor_select_heads(const float *echo_host, const float *induction_host,
+                       int n_heads, int group, double frac_induction, double frac_echo,
+                       uint8_t *mask_host);
+
+/*
  * Measurement hook.  After this call, every razor_decode_attn issued by the calling
  * thread records ev_start (a hipEvent_t) on its stream right before the kernel that
  * streams the cache and ev_stop right after it, so a benchmark can time that kernel

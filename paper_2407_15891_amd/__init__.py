@@ -1,7 +1,8 @@
 """Python binding of the razor C-ABI library (RazorAttention hot path on MI355X).
 
 The functions `razor_plan`, `razor_compress`, `razor_column_sums`, `razor_decode_attn`,
-`razor_profile_events` and `razor_strerror` carry the names and the argument order of `include/razor.h`; they only marshal
+`razor_head_scores`, `razor_head_scores_workspace`, `razor_select_heads`, `razor_profile_events`
+and `razor_strerror` carry the names and the argument order of `include/razor.h`; they only marshal
 arguments (torch tensors -> device pointers, numpy arrays -> host pointers).  Every
 step of the path runs in the HIP kernels of `librazor.so`; there is no Python or CPU
 fallback: a missing library raises on first use.
@@ -28,6 +29,7 @@ RAZOR_MAX_GROUP = 16
 RAZOR_MAX_WORKERS = 8192
 
 EXPORTS = ("razor_plan", "razor_compress", "razor_column_sums", "razor_decode_attn",
+           "razor_head_scores_workspace", "razor_head_scores", "razor_select_heads",
            "razor_profile_events", "razor_strerror")
 
 
@@ -89,6 +91,14 @@ def load_library():
     L.razor_column_sums.argtypes = [PP, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
     L.razor_decode_attn.restype = ctypes.c_int
     L.razor_decode_attn.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    ci = ctypes.c_int
+    L.razor_head_scores_workspace.restype = sz
+    L.razor_head_scores_workspace.argtypes = [ci, ci]
+    L.razor_head_scores.restype = ci
+    L.razor_head_scores.argtypes = [vp, vp, ci, ci, ci, ci, ci, i64, i64, i64, i64, ctypes.c_float, ci, ci,
+                                    vp, vp, vp, sz, vp]
+    L.razor_select_heads.restype = ci
+    L.razor_select_heads.argtypes = [vp, vp, ci, ci, ctypes.c_double, ctypes.c_double, vp]
     L.razor_profile_events.restype = ctypes.c_int
     L.razor_profile_events.argtypes = [vp, vp]
     L.razor_strerror.restype = ctypes.c_char_p
@@ -151,6 +161,27 @@ def razor_decode_attn(params: RazorParams, Q, k_new, v_new, arena, comp, desc_de
         _dev(desc_dev), _dev(O), _dev(workspace), workspace_bytes, stream or None)
 
 
+def razor_head_scores_workspace(n_q_heads: int, n_tokens: int) -> int:
+    return load_library().razor_head_scores_workspace(n_q_heads, n_tokens)
+
+
+def razor_head_scores(Q, K, dtype: int, n_q_heads: int, n_kv_heads: int, head_dim: int, n_tokens: int,
+                      q_stride_h: int, q_stride_n: int, k_stride_h: int, k_stride_n: int, scale: float,
+                      period: int, all_copies: int, echo, induction, workspace, workspace_bytes: int,
+                      stream: int = 0) -> int:
+    return load_library().razor_head_scores(
+        _dev(Q), _dev(K), dtype, n_q_heads, n_kv_heads, head_dim, n_tokens, q_stride_h, q_stride_n,
+        k_stride_h, k_stride_n, scale, period, all_copies, _dev(echo), _dev(induction), _dev(workspace),
+        workspace_bytes, stream or None)
+
+
+def razor_select_heads(echo_host: np.ndarray, induction_host: np.ndarray, n_heads: int, group: int,
+                       frac_induction: float, frac_echo: float, mask_host: np.ndarray) -> int:
+    assert echo_host.dtype == np.float32 and induction_host.dtype == np.float32 and mask_host.dtype == np.uint8
+    return load_library().razor_select_heads(_host(echo_host), _host(induction_host), n_heads, group,
+                                             frac_induction, frac_echo, _host(mask_host))
+
+
 def razor_profile_events(ev_start, ev_stop) -> int:
     """ev_start / ev_stop: raw hipEvent_t handles (ctypes.c_void_p) or None."""
     return load_library().razor_profile_events(ev_start, ev_stop)
@@ -159,6 +190,33 @@ def razor_profile_events(ev_start, ev_stop) -> int:
 def _check(status: int, where: str) -> None:
     if status != RAZOR_OK:
         raise RazorError(status, where)
+
+
+def head_scores(Q, K, scale: float, period: int, all_copies: bool = False):
+    """(echo, induction) float32 device tensors [H_q] for Q [H_q, N, d], K [H_kv, N, d] (bf16 device
+    tensors, last dimension contiguous) of a prompt that repeats every `period` tokens."""
+    import torch
+    assert Q.dtype == torch.bfloat16 and K.dtype == torch.bfloat16 and Q.stride(2) == 1 and K.stride(2) == 1
+    Hq, N, d = Q.shape
+    assert K.shape[1:] == (N, d)
+    ws_bytes = razor_head_scores_workspace(Hq, N)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=Q.device)
+    echo = torch.empty(Hq, dtype=torch.float32, device=Q.device)
+    induction = torch.empty(Hq, dtype=torch.float32, device=Q.device)
+    _check(razor_head_scores(Q, K, RAZOR_BF16, Hq, K.shape[0], d, N, Q.stride(0), Q.stride(1), K.stride(0),
+                             K.stride(1), scale, period, int(bool(all_copies)), echo, induction, ws, ws.numel(),
+                             torch.cuda.current_stream(Q.device).cuda_stream), "razor_head_scores")
+    return echo, induction
+
+
+def select_heads(echo, induction, group: int, frac_induction: float = 0.14, frac_echo: float = 0.01) -> np.ndarray:
+    """uint8 retrieval mask [n_heads / group] from per-query-head scores (host arrays, all layers)."""
+    e = np.ascontiguousarray(echo, dtype=np.float32)
+    i = np.ascontiguousarray(induction, dtype=np.float32)
+    assert e.ndim == 1 and e.shape == i.shape
+    mask = np.zeros(max(len(e) // max(group, 1), 1), np.uint8)
+    _check(razor_select_heads(e, i, len(e), group, frac_induction, frac_echo, mask), "razor_select_heads")
+    return mask
 
 
 class RazorCache:

@@ -2,6 +2,8 @@
 // Algorithm 1 (steps 2-3), buffer sizes and error text.  No GPU work happens here.
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 
@@ -155,6 +157,29 @@ extern "C" int razor_plan(const razor_params *p, const int32_t *seq_lens_host,
             for (int32_t t = 0; t < e.rows; ++t) out[t] = t < head ? t : t + e.n_dropped;
         }
     }
+    return RAZOR_OK;
+}
+
+extern "C" int razor_select_heads(const float *echo_host, const float *induction_host, int n_heads,
+                                  int group, double frac_induction, double frac_echo,
+                                  uint8_t *mask_host)
+{
+    if (!echo_host || !induction_host || !mask_host || n_heads <= 0 || group <= 0 || n_heads % group)
+        return RAZOR_EINVAL;
+    if (!(frac_induction >= 0.0 && frac_induction <= 1.0) || !(frac_echo >= 0.0 && frac_echo <= 1.0))
+        return RAZOR_EINVAL;
+    for (int i = 0; i < n_heads; ++i)
+        if (std::isnan(echo_host[i]) || std::isnan(induction_host[i])) return RAZOR_EINVAL;
+    std::fill(mask_host, mask_host + n_heads / group, (uint8_t)0);
+    std::vector<int> order(n_heads);
+    const auto protect = [&](const float *score, double frac) {
+        const int count = (int)std::floor(frac * n_heads + 0.5);
+        for (int i = 0; i < n_heads; ++i) order[i] = i;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return score[a] > score[b]; });
+        for (int k = 0; k < count; ++k) mask_host[order[k] / group] = 1;   // OR over the group
+    };
+    protect(induction_host, frac_induction);
+    protect(echo_host, frac_echo);
     return RAZOR_OK;
 }
 

@@ -213,3 +213,51 @@ def test_plan_random_tables_match_oracle():
                 assert grow <= e["cap"] < grow + 16, trial
                 total += len(kept); off += e["cap"]
         assert sizes.total_rows == total and sizes.total_cap == off
+
+
+# ----------------------------------------------------------------- head selection (Sec. 3.3)
+def test_select_heads_matches_oracle_on_random_scores():
+    rng = np.random.default_rng(8)
+    for trial in range(200):
+        group = int(rng.choice([1, 2, 4, 8]))
+        n = group * int(rng.integers(1, 65))
+        # few distinct values: plenty of ties, so the tie rule is exercised
+        echo = rng.integers(0, 6, n).astype(np.float32) / 5
+        ind = rng.integers(0, 6, n).astype(np.float32) / 5
+        fi, fe = float(rng.uniform(0, 0.5)), float(rng.uniform(0, 0.2))
+        got = razor.select_heads(echo, ind, group, fi, fe)
+        np.testing.assert_array_equal(got, orc.select_heads(echo, ind, group, fi, fe), err_msg=f"trial {trial}")
+    got = razor.select_heads(np.linspace(0, 1, 1024), np.linspace(1, 0, 1024), 1)
+    assert got.sum() == 143 + 10 and got[:143].all() and got[-10:].all()          # Table 2's fractions
+
+
+def test_select_heads_rejects_bad_arguments():
+    e = np.zeros(8, np.float32)
+    m = np.zeros(8, np.uint8)
+    assert razor.razor_select_heads(e, e, 8, 3, 0.1, 0.1, m) == razor.RAZOR_EINVAL     # 8 % 3
+    assert razor.razor_select_heads(e, e, 8, 2, 1.5, 0.1, m) == razor.RAZOR_EINVAL
+    assert razor.razor_select_heads(e, e, 8, 2, 0.1, -0.1, m) == razor.RAZOR_EINVAL
+    assert razor.razor_select_heads(e, e, 0, 1, 0.1, 0.1, m) == razor.RAZOR_EINVAL
+    bad = e.copy(); bad[3] = np.nan
+    assert razor.razor_select_heads(bad, e, 8, 2, 0.1, 0.1, m) == razor.RAZOR_EINVAL
+    assert razor.razor_select_heads(e, e, 8, 2, 0.1, 0.1, m) == razor.RAZOR_OK
+
+
+def test_head_scores_arguments_are_checked_before_any_gpu_work():
+    L = razor.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    ok = dict(dtype=razor.RAZOR_BF16, hq=8, hkv=2, d=128, n=1000, qsh=128000, qsn=128, ksh=128000, ksn=128,
+              scale=0.088, period=250)
+
+    def call(ws_bytes=1 << 30, Q=fake, **kw):
+        a = dict(ok, **kw)
+        return L.razor_head_scores(Q, fake, a["dtype"], a["hq"], a["hkv"], a["d"], a["n"], a["qsh"], a["qsn"],
+                                   a["ksh"], a["ksn"], a["scale"], a["period"], 0, fake, fake, fake, ws_bytes, None)
+    for kw in (dict(dtype=razor.RAZOR_F32), dict(d=96), dict(hq=7), dict(hkv=0), dict(period=0), dict(period=1000),
+               dict(n=1), dict(scale=0.0), dict(scale=float("nan")), dict(qsn=64), dict(ksn=132), dict(qsh=-8),
+               dict(Q=None), dict(Q=ctypes.c_void_p(0x1008)), dict(hq=70000, hkv=70000)):
+        assert call(**kw) == razor.RAZOR_EINVAL, kw
+    need = razor.razor_head_scores_workspace(8, 1000)
+    assert need == 8 * 4 * 4 * 2 * 4                                  # 4 tiles of 256 queries, 4 waves, 2 sums
+    assert call(ws_bytes=need - 1) == razor.RAZOR_ECAPACITY
+    assert razor.razor_head_scores_workspace(0, 10) == 0
