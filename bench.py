@@ -183,6 +183,66 @@ def run_stack(args, ev):
     print(json.dumps(result))
 
 
+def run_head_scores(args, ev):
+    """Sec. 3.3 on the paper's prompt size.  One step = every head of --layers layers scored once."""
+    import numpy as np
+    import torch
+    import paper_2407_15891_amd as razor
+    from paper_2407_15891_amd.workloads import make_scoring_workload
+
+    dev = "cuda:0"
+    layers = args.layers or 8
+    w = make_scoring_workload(dev, n_q_heads=32, n_kv_heads=8, head_dim=128, period=2500, seed=1)
+    Q = w.Q.repeat(layers, 1, 1)                     # layers stacked along the head dimension
+    K = w.K.repeat(layers, 1, 1)
+    Hq, N, d = Q.shape
+    stream = torch.cuda.current_stream().cuda_stream
+    ws = torch.empty(razor.razor_head_scores_workspace(Hq, N), dtype=torch.uint8, device=dev)
+    echo = torch.empty(Hq, dtype=torch.float32, device=dev)
+    ind = torch.empty(Hq, dtype=torch.float32, device=dev)
+
+    def step():
+        rc = razor.razor_head_scores(Q, K, razor.RAZOR_BF16, Hq, K.shape[0], d, N, Q.stride(0), Q.stride(1),
+                                     K.stride(0), K.stride(1), w.scale, w.period, 0, echo, ind, ws, ws.numel(), stream)
+        assert rc == 0, razor.razor_strerror(rc)
+    steps, warmup = min(args.steps, 20), min(args.warmup, 3)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    a, b = ev.create(), ev.create()
+    t0 = time.perf_counter()
+    ev.record(a, stream)
+    for _ in range(steps):
+        step()
+    ev.record(b, stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = ev.elapsed_ms(a, b) / steps
+    flops = Hq * (N * (N + 1) // 2) * 2 * d         # causal half of Q K^T, multiply + add
+    tflops = flops / (kernel_ms * 1e-3) / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import razor_oracle as orc
+        n_small = 5000                                # the oracle on 16 heads of a 5000-token prompt
+        ws_small = make_scoring_workload("cpu", n_q_heads=16, n_kv_heads=4, head_dim=128, period=1250, seed=1)
+        t1 = time.perf_counter()
+        orc.head_scores(ws_small.Q, ws_small.K, ws_small.scale, ws_small.period)
+        dt = time.perf_counter() - t1
+        cpu = {"value": 16 * (n_small * (n_small + 1) // 2) * 2 * 128 / dt / 1e12, "unit": "TFLOP/s",
+               "cores": min(16, os.cpu_count() or 1), "kind": "oracle",
+               "sample": "16 heads x 128 of a 5000-token prompt (period 1250), fp64"}
+    print(json.dumps({
+        "metric": "head-scoring pass (Sec. 3.3) causal QK^T TFLOP/s", "value": tflops, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall / steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"2500 random tokens x 4, {layers} layers of 32/8 heads x 128, one call"},
+        "heads_per_s": Hq / (kernel_ms * 1e-3),
+        "roofline": {"bound": "mfma", "kernel": "head_scores_kernel<128>", "achieved": tflops, "peak": 2500.0,
+                     "unit": "TFLOP/s", "frac": tflops / 2500.0, "kernel_ms": kernel_ms, "traffic": None},
+        "cpu_baseline": cpu,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -201,6 +261,9 @@ def main():
                     "step per rotated cache (removes host launch overhead; matters for small configs)")
     ap.add_argument("--alibi", action="store_true", help="ALiBi form: Eq.(1) logit bias, no sinks, no "
                     "compensation token, per-head buffer lengths (retrieval heads keep everything)")
+    ap.add_argument("--head-scores", action="store_true", help="time the head-scoring pass of Sec. 3.3 instead "
+                    "(2500 random tokens x 4, --layers layers of 32/8 heads x 128 stacked in one call); prints "
+                    "its own JSON line, bound by the matrix cores")
     ap.add_argument("--pmc-calib", action="store_true", help="also run one plain 1 GiB device copy, the "
                     "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
@@ -221,6 +284,8 @@ def main():
     torch.cuda.set_device(0)
     ev = HipEvents()
 
+    if args.head_scores:
+        return run_head_scores(args, ev)
     if args.config == 5:
         return run_stack(args, ev)
 

@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <type_traits>
 
 #include "razor.h"
 #include "razor_device.h"
@@ -24,11 +25,14 @@ constexpr int kQueriesPerWave = 64;                       // four 16-query opera
 constexpr int kQueryTiles = kQueriesPerWave / 16;
 constexpr int kQueriesPerGroup = 4 * kQueriesPerWave;     // one workgroup of four wavefronts
 constexpr int kStageKeys = 64;                            // keys staged in LDS per step
-constexpr int kKeyTiles = kStageKeys / 16;
+constexpr int kStepKeys = 32;                             // keys per pipeline step
+constexpr int kStepTiles = kStepKeys / 16;
 constexpr float kLowest = -1.0e30f;                       // finite "no key seen yet"
 constexpr float kMinusInf = -__builtin_huge_valf();
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+// max(a, b) as the median of (a, b, +inf): one instruction, no NaN quieting of the operands
+__device__ __forceinline__ float max_of(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_huge_valf()); }
 
 // Dot product of two 16-byte pieces of bf16 (fp32 products and sums, element order).
 __device__ __forceinline__ float dot_piece(const uint4 a, const uint4 b, float acc)
@@ -66,7 +70,7 @@ __global__ __launch_bounds__(256, 2) void head_scores_kernel(
 
     const int tile = n_tiles - 1 - (int)blockIdx.x;   // longest rows first
     const int head = blockIdx.y;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int kg = lane >> 4, n = lane & 15;
     const int q0 = tile * kQueriesPerGroup;           // first query of the workgroup
     const int qw0 = q0 + wave * kQueriesPerWave;      // first query of this wave
@@ -94,77 +98,141 @@ __global__ __launch_bounds__(256, 2) void head_scores_kernel(
     }
 
     const int n_stages = (min(q0 + kQueriesPerGroup, n_tokens) + kStageKeys - 1) / kStageKeys;
-    uint4 hold[LOADS];
-    auto fetch = [&](int st, uint4(&hold)[LOADS]) {
+    static_assert(LOADS == 2 || LOADS == 4, "a thread moves two or four pieces per stage");
+    // Staging: thread t moves pieces t, t + 256, ... of a stage (row-major, coalesced).  The
+    // source pointers advance by one stage per step; rows past the prompt read its last row.
+    const int64_t stage_elems = (int64_t)kStageKeys * k_stride_n;
+    const uint16_t *src[LOADS], *tail[LOADS];
+    int src_row[LOADS], dst[LOADS];
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const int idx = j * 256 + (int)threadIdx.x;
-            const int row = min(st * kStageKeys + idx / LPR, last);
-            hold[j] = *reinterpret_cast<const uint4 *>(Kh + (int64_t)row * k_stride_n + (idx % LPR) * 8);
+    for (int j = 0; j < LOADS; ++j) {
+        const int idx = j * 256 + (int)threadIdx.x;
+        const int row = idx / LPR, c = idx % LPR;
+        src_row[j] = row;
+        src[j] = Kh + (int64_t)row * k_stride_n + c * 8;
+        tail[j] = Kh + (int64_t)last * k_stride_n + c * 8;
+        dst[j] = ((row >> 4) * LPR + c) * 16 + ((row & 15) ^ c);
+    }
+    // Named registers, not an array: the loads stay in registers across the barrier.
+    uint4 hold0, hold1, hold2 = {}, hold3 = {};
+    auto fetch_piece = [&](int st, int j) {
+        const uint16_t *from = st * kStageKeys + src_row[j] > last ? tail[j] : src[j] + st * stage_elems;
+        return *reinterpret_cast<const uint4 *>(from);
+    };
+    auto fetch = [&](int st) {
+        hold0 = fetch_piece(st, 0);
+        hold1 = fetch_piece(st, 1);
+        if constexpr (LOADS == 4) {
+            hold2 = fetch_piece(st, 2);
+            hold3 = fetch_piece(st, 3);
         }
     };
-    auto deposit = [&](int buf, const uint4(&hold)[LOADS]) {
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const int idx = j * 256 + (int)threadIdx.x;
-            const int row = idx / LPR, c = idx % LPR;
-            stage[buf][((row >> 4) * LPR + c) * 16 + ((row & 15) ^ c)] = hold[j];
+    auto deposit = [&](int buf) {
+        stage[buf][dst[0]] = hold0;
+        stage[buf][dst[1]] = hold1;
+        if constexpr (LOADS == 4) {
+            stage[buf][dst[2]] = hold2;
+            stage[buf][dst[3]] = hold3;
         }
     };
 
-    fetch(0, hold);
-    deposit(0, hold);
-    __syncthreads();
-    for (int st = 0; st < n_stages; ++st) {
-        // the last step fetches its own stage again and parks it in the idle buffer: no branch
-        // around the loads keeps them in registers across the arithmetic
-        fetch(min(st + 1, n_stages - 1), hold);
-        const int k0 = st * kStageKeys;
-        if (k0 <= qw0) {                               // not entirely right of the wave's diagonal
-            const bool diagonal = k0 == qw0;
-            const uint4 *buf = stage[st & 1];
-            f32x4 S[kQueryTiles][kKeyTiles];
+    // One pipeline step covers 32 keys (two key tiles) against the wave's 64 queries.
+    auto products = [&](int u, f32x4(&S)[kQueryTiles][kStepTiles]) {
+        const uint4 *buf = stage[(u >> 1) & 1];
 #pragma unroll
-            for (int kt = 0; kt < kKeyTiles; ++kt) {
-                bf16x8 a[NS];
+        for (int kt = 0; kt < kStepTiles; ++kt) {
+            const int tile = (u & 1) * kStepTiles + kt;
+            bf16x8 a[NS];
 #pragma unroll
-                for (int s = 0; s < NS; ++s) {
-                    const int c = 4 * s + kg;
-                    a[s] = __builtin_bit_cast(bf16x8, buf[(kt * LPR + c) * 16 + (n ^ c)]);
-                }
-#pragma unroll
-                for (int qt = 0; qt < kQueryTiles; ++qt) {
-                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int s = 0; s < NS; ++s)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s], qreg[qt][s], acc, 0, 0, 0);
-                    S[qt][kt] = acc;
-                }
+            for (int s = 0; s < NS; ++s) {
+                const int c = 4 * s + kg;
+                a[s] = __builtin_bit_cast(bf16x8, buf[(tile * LPR + c) * 16 + (n ^ c)]);
             }
 #pragma unroll
             for (int qt = 0; qt < kQueryTiles; ++qt) {
-                if (diagonal) {                        // key k0 + 16 kt + 4 kg + r against query qw0 + 16 qt + n
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int kt = 0; kt < kKeyTiles; ++kt)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (kt * 16 + 4 * kg + r > qt * 16 + n) S[qt][kt][r] = kMinusInf;
-                }
-                float raw = kMinusInf;
-#pragma unroll
-                for (int kt = 0; kt < kKeyTiles; ++kt)
-                    raw = fmaxf(fmaxf(raw, fmaxf(S[qt][kt][0], S[qt][kt][1])), fmaxf(S[qt][kt][2], S[qt][kt][3]));
-                const float top = fmaxf(m[qt], raw * scale_log2e);   // stays finite: m starts finite
-                float sum = l[qt] * exp2_fast(m[qt] - top);
-#pragma unroll
-                for (int kt = 0; kt < kKeyTiles; ++kt)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) sum += exp2_fast(fmaf(S[qt][kt][r], scale_log2e, -top));
-                m[qt] = top;
-                l[qt] = sum;
+                for (int s = 0; s < NS; ++s)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s], qreg[qt][s], acc, 0, 0, 0);
+                S[qt][kt] = acc;
             }
         }
-        deposit((st + 1) & 1, hold);
+    };
+    auto absorb = [&](int u, f32x4(&S)[kQueryTiles][kStepTiles], auto masked) {
+        const int k0 = u * kStepKeys;
+#pragma unroll
+        for (int qt = 0; qt < kQueryTiles; ++qt) {
+            if (masked) {                      // key k0 + 16 kt + 4 kg + r against query qw0 + 16 qt + n
+#pragma unroll
+                for (int kt = 0; kt < kStepTiles; ++kt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (k0 + kt * 16 + 4 * kg + r > qw0 + qt * 16 + n) S[qt][kt][r] = kMinusInf;
+            }
+            float raw = kMinusInf;
+#pragma unroll
+            for (int kt = 0; kt < kStepTiles; ++kt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) raw = max_of(raw, S[qt][kt][r]);
+            const float top = max_of(m[qt], raw * scale_log2e);   // stays finite: m starts finite
+            float sum = l[qt] * exp2_fast(m[qt] - top);
+#pragma unroll
+            for (int kt = 0; kt < kStepTiles; ++kt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) sum += exp2_fast(fmaf(S[qt][kt][r], scale_log2e, -top));
+            m[qt] = top;
+            l[qt] = sum;
+        }
+    };
+    // A step in the interior of the causal region: the maximum / sum update of its logits (`cur`)
+    // is issued together with the products of the next step (`nxt`) in one straight block, so
+    // that the vector unit and the matrix cores of a SIMD work at the same time.
+    auto plain_step = [&](int u, f32x4(&cur)[kQueryTiles][kStepTiles], f32x4(&nxt)[kQueryTiles][kStepTiles]) {
+        products(u + 1, nxt);
+        absorb(u, cur, std::false_type{});
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * NS, 0);     // LDS reads of the key tiles
+        __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);         // vector work while they land
+#pragma unroll
+        for (int i = 0; i < kQueryTiles * kStepTiles * NS; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one matrix instruction
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);      // three vector instructions
+            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);      // one exp2
+        }
+    };
+
+    // Stage `diag` holds the wave's own keys (masked per element); the stages before it are
+    // interior, the stages after it lie right of the diagonal and only need this wave's share of
+    // the staging.  Three loops instead of one loop with branches: no register shuffling where
+    // control flow would merge.  Every wave passes the same number of barriers.
+    const int diag = qw0 / kStageKeys;
+    const bool active = diag < n_stages;               // false: the wave lies past the prompt
+    const int interior = active ? diag : 0;
+    f32x4 S0[kQueryTiles][kStepTiles], S1[kQueryTiles][kStepTiles];
+    fetch(0);
+    deposit(0);
+    __syncthreads();
+    if (active) products(0, S0);
+    int st = 0;
+    for (; st < interior; ++st) {
+        fetch(st + 1);                            // st + 1 <= diag < n_stages
+        plain_step(2 * st, S0, S1);
+        deposit((st + 1) & 1);
+        __syncthreads();
+        plain_step(2 * st + 1, S1, S0);                 // its products read the stage deposited just now
+    }
+    if (active) {
+        // the last stage of the workgroup fetches itself again and parks it in the idle buffer
+        fetch(min(st + 1, n_stages - 1));
+        products(2 * st + 1, S1);
+        absorb(2 * st, S0, std::true_type{});
+        deposit((st + 1) & 1);
+        __syncthreads();
+        absorb(2 * st + 1, S1, std::true_type{});
+        ++st;
+    }
+    for (; st < n_stages; ++st) {
+        fetch(min(st + 1, n_stages - 1));
+        deposit((st + 1) & 1);
         __syncthreads();
     }
 
