@@ -21,7 +21,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kQueriesPerWave = 64;                       // four 16-query operand tiles
+constexpr int kQueriesPerWave = 32;                       // two 16-query operand tiles
 constexpr int kQueryTiles = kQueriesPerWave / 16;
 constexpr int kQueriesPerGroup = 4 * kQueriesPerWave;     // one workgroup of four wavefronts
 constexpr int kStageKeys = 64;                            // keys staged in LDS per step
@@ -57,7 +57,7 @@ __device__ __forceinline__ float dot_piece(const uint4 a, const uint4 b, float a
 //   sum of a query stay inside a lane until the four key groups are merged at the very end.
 // Stages right of the diagonal are skipped, the diagonal stage is masked per element.
 template <int D>
-__global__ __launch_bounds__(256, 2) void head_scores_kernel(
+__global__ __launch_bounds__(256, 3) void head_scores_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, int64_t q_stride_h,
     int64_t q_stride_n, int64_t k_stride_h, int64_t k_stride_n, int n_tokens, int group,
     int period, int all_copies, float scale_log2e, int n_tiles, float *__restrict__ partial)
@@ -188,6 +188,7 @@ __global__ __launch_bounds__(256, 2) void head_scores_kernel(
     // is issued together with the products of the next step (`nxt`) in one straight block, so
     // that the vector unit and the matrix cores of a SIMD work at the same time.
     auto plain_step = [&](int u, f32x4(&cur)[kQueryTiles][kStepTiles], f32x4(&nxt)[kQueryTiles][kStepTiles]) {
+        __builtin_amdgcn_sched_barrier(0);                          // a scheduling region of its own
         products(u + 1, nxt);
         absorb(u, cur, std::false_type{});
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * NS, 0);     // LDS reads of the key tiles
@@ -198,6 +199,7 @@ __global__ __launch_bounds__(256, 2) void head_scores_kernel(
             __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);      // three vector instructions
             __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);      // one exp2
         }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     // Stage `diag` holds the wave's own keys (masked per element); the stages before it are

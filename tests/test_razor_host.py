@@ -258,6 +258,6 @@ def test_head_scores_arguments_are_checked_before_any_gpu_work():
                dict(Q=None), dict(Q=ctypes.c_void_p(0x1008)), dict(hq=70000, hkv=70000)):
         assert call(**kw) == razor.RAZOR_EINVAL, kw
     need = razor.razor_head_scores_workspace(8, 1000)
-    assert need == 8 * 4 * 4 * 2 * 4                                  # 4 tiles of 256 queries, 4 waves, 2 sums
+    assert need == 8 * 8 * 4 * 2 * 4                                  # 8 tiles of 128 queries, 4 waves, 2 sums
     assert call(ws_bytes=need - 1) == razor.RAZOR_ECAPACITY
     assert razor.razor_head_scores_workspace(0, 10) == 0
