@@ -20,18 +20,18 @@ namespace razor {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kQueriesPerWave = 32;                       // two 16-query operand tiles
-constexpr int kQueryTiles = kQueriesPerWave / 16;
+constexpr int kQueriesPerWave = 32;                       // one 32-query operand tile
 constexpr int kQueriesPerGroup = 4 * kQueriesPerWave;     // one workgroup of four wavefronts
-constexpr int kStageKeys = 64;                            // keys staged in LDS per step
-constexpr int kStepKeys = 32;                             // keys per pipeline step
-constexpr int kStepTiles = kStepKeys / 16;
+constexpr int kStageKeys = 64;                            // keys staged in LDS per barrier
+constexpr int kStepKeys = 32;                             // keys per pipeline step: one 32-key tile
 constexpr float kLowest = -1.0e30f;                       // finite "no key seen yet"
 constexpr float kMinusInf = -__builtin_huge_valf();
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
-// max(a, b) as the median of (a, b, +inf): one instruction, no NaN quieting of the operands
+// max(a, b) as the median of (a, b, +inf): no NaN quieting of the operands, and the compiler
+// pairs two of them into one three-operand maximum
 __device__ __forceinline__ float max_of(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_huge_valf()); }
 
 // Dot product of two 16-byte pieces of bf16 (fp32 products and sums, element order).
@@ -46,15 +46,19 @@ __device__ __forceinline__ float dot_piece(const uint4 a, const uint4 b, float a
     return acc;
 }
 
-// Workgroup (tile, head): 256 consecutive query rows of one head, 64 per wavefront, against
+// Workgroup (tile, head): 128 consecutive query rows of one head, 32 per wavefront, against
 // keys 0 .. last query of the tile in stages of 64 keys.
 //
-// Lane l = 16 * kg + n.  A stage of keys is staged in LDS piece-major per 16-key tile (16-byte
-// piece c of key r at slot c * 16 + (r ^ c): the xor spreads the row-major global loads over
+// Lane l = 32 * g + r.  A stage of keys is staged in LDS piece-major per 32-key tile (16-byte
+// piece c of key j at slot c * 32 + (j ^ c): the xor spreads the row-major global loads over
 // the banks, and a wave still reads one contiguous kilobyte per matrix-core operand).
-//   S^T[key][query] = K[key][:] . Q[query][:]   v_mfma_f32_16x16x32_bf16, A = key tile, B = Q
-//   lane (kg, n) gets query n of the tile and keys 4 kg .. 4 kg + 3: the running maximum and
-//   sum of a query stay inside a lane until the four key groups are merged at the very end.
+//   S^T[key][query] = K[key][:] . Q[query][:]   v_mfma_f32_32x32x16_bf16, A = key tile, B = Q
+//   lane (g, r) gets query r of the wave and, in accumulator register v, key
+//   8 (v / 4) + 4 g + v % 4 of the tile: the running maximum and sum of a query stay inside a
+//   lane until the two key halves are merged at the very end.
+// The 32x32 shape halves the matrix instructions per logit against 16x16x32; what bounds this
+// kernel is the vector unit (one fma, one exp2, one add per logit), and every matrix
+// instruction costs it about two issue slots whatever its size.
 // Stages right of the diagonal are skipped, the diagonal stage is masked per element.
 template <int D>
 __global__ __launch_bounds__(256, 3) void head_scores_kernel(
@@ -62,7 +66,7 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
     int64_t q_stride_n, int64_t k_stride_h, int64_t k_stride_n, int n_tokens, int group,
     int period, int all_copies, float scale_log2e, int n_tiles, float *__restrict__ partial)
 {
-    constexpr int NS = D / 32;        // contraction steps of 32 columns
+    constexpr int NS = D / 16;        // contraction steps of 16 columns
     constexpr int LPR = D / 8;        // 16-byte pieces per row
     constexpr int STAGE = kStageKeys * LPR;          // pieces per stage
     constexpr int LOADS = STAGE / 256;               // pieces per thread per stage
@@ -71,52 +75,44 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
     const int tile = n_tiles - 1 - (int)blockIdx.x;   // longest rows first
     const int head = blockIdx.y;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int kg = lane >> 4, n = lane & 15;
+    const int g = lane >> 5, r = lane & 31;
     const int q0 = tile * kQueriesPerGroup;           // first query of the workgroup
     const int qw0 = q0 + wave * kQueriesPerWave;      // first query of this wave
     const uint16_t *Qh = Q + (int64_t)head * q_stride_h;
     const uint16_t *Kh = K + (int64_t)(head / group) * k_stride_h;
     const int last = n_tokens - 1;
 
-    // B operands: the wave's 64 queries, 16 per tile (rows past the prompt repeat the last one)
-    bf16x8 qreg[kQueryTiles][NS];
-#pragma unroll
-    for (int qt = 0; qt < kQueryTiles; ++qt) {
-        const int row = min(qw0 + qt * 16 + n, last);
+    // B operands: the wave's 32 queries (rows past the prompt repeat the last one); lane (g, r)
+    // holds pieces g, 2 + g, 4 + g, ... of query r
+    bf16x8 qreg[NS];
+    {
+        const int row = min(qw0 + r, last);
 #pragma unroll
         for (int s = 0; s < NS; ++s)
-            qreg[qt][s] = __builtin_bit_cast(
-                bf16x8, *reinterpret_cast<const uint4 *>(Qh + (int64_t)row * q_stride_n + (4 * s + kg) * 8));
+            qreg[s] = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const uint4 *>(Qh + (int64_t)row * q_stride_n + (2 * s + g) * 8));
     }
 
-    // running maximum (already times scale * log2 e) and sum of 2^(logit - maximum), per query tile
-    float m[kQueryTiles], l[kQueryTiles];
-#pragma unroll
-    for (int qt = 0; qt < kQueryTiles; ++qt) {
-        m[qt] = kLowest;
-        l[qt] = 0.f;
-    }
+    // running maximum (already times scale * log2 e) and sum of 2^(logit - maximum)
+    float m = kLowest, l = 0.f;
 
     const int n_stages = (min(q0 + kQueriesPerGroup, n_tokens) + kStageKeys - 1) / kStageKeys;
     static_assert(LOADS == 2 || LOADS == 4, "a thread moves two or four pieces per stage");
     // Staging: thread t moves pieces t, t + 256, ... of a stage (row-major, coalesced).  The
     // source pointers advance by one stage per step; rows past the prompt read its last row.
+    // Piece j of a thread sits 256 / LPR rows below piece j - 1, in the same column: one pointer,
+    // one row number and one LDS slot per thread, the rest are constant offsets.
+    constexpr int ROWS_PER_LOAD = 256 / LPR;
     const int64_t stage_elems = (int64_t)kStageKeys * k_stride_n;
-    const uint16_t *src[LOADS], *tail[LOADS];
-    int src_row[LOADS], dst[LOADS];
-#pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-        const int idx = j * 256 + (int)threadIdx.x;
-        const int row = idx / LPR, c = idx % LPR;
-        src_row[j] = row;
-        src[j] = Kh + (int64_t)row * k_stride_n + c * 8;
-        tail[j] = Kh + (int64_t)last * k_stride_n + c * 8;
-        dst[j] = ((row >> 4) * LPR + c) * 16 + ((row & 15) ^ c);
-    }
-    // Named registers, not an array: the loads stay in registers across the barrier.
-    uint4 hold0, hold1, hold2 = {}, hold3 = {};
+    const int64_t load_elems = (int64_t)ROWS_PER_LOAD * k_stride_n;
+    const int row0 = (int)threadIdx.x / LPR, col = (int)threadIdx.x % LPR;
+    const uint16_t *src = Kh + (int64_t)row0 * k_stride_n + col * 8;
+    const uint16_t *tail = Kh + (int64_t)last * k_stride_n + col * 8;
+    auto slot_of = [&](int row) { return ((row >> 5) * LPR + col) * 32 + ((row & 31) ^ col); };
+    uint4 hold0, hold1, hold2 = {}, hold3 = {};   // named registers: they stay in registers across the barrier
     auto fetch_piece = [&](int st, int j) {
-        const uint16_t *from = st * kStageKeys + src_row[j] > last ? tail[j] : src[j] + st * stage_elems;
+        const uint16_t *from = st * kStageKeys + row0 + j * ROWS_PER_LOAD > last ? tail
+                                                                                  : src + st * stage_elems + j * load_elems;
         return *reinterpret_cast<const uint4 *>(from);
     };
     auto fetch = [&](int st) {
@@ -128,108 +124,113 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
         }
     };
     auto deposit = [&](int buf) {
-        stage[buf][dst[0]] = hold0;
-        stage[buf][dst[1]] = hold1;
+        stage[buf][slot_of(row0)] = hold0;
+        stage[buf][slot_of(row0 + ROWS_PER_LOAD)] = hold1;
         if constexpr (LOADS == 4) {
-            stage[buf][dst[2]] = hold2;
-            stage[buf][dst[3]] = hold3;
+            stage[buf][slot_of(row0 + 2 * ROWS_PER_LOAD)] = hold2;
+            stage[buf][slot_of(row0 + 3 * ROWS_PER_LOAD)] = hold3;
         }
     };
 
-    // One pipeline step covers 32 keys (two key tiles) against the wave's 64 queries.
-    auto products = [&](int u, f32x4(&S)[kQueryTiles][kStepTiles]) {
-        const uint4 *buf = stage[(u >> 1) & 1];
+    // One pipeline step covers one 32-key tile against the wave's 32 queries.  The LDS slot of
+    // piece 2 s + g of key r inside a tile is kept per lane; buffer and tile are compile-time
+    // constants of a step, so they end up in the offset field of the LDS reads.
+    int slot[NS];
 #pragma unroll
-        for (int kt = 0; kt < kStepTiles; ++kt) {
-            const int tile = (u & 1) * kStepTiles + kt;
-            bf16x8 a[NS];
+    for (int s = 0; s < NS; ++s) slot[s] = (2 * s + g) * 32 + (r ^ (2 * s + g));
+    auto products = [&](auto buf_tile, f32x16 &S) {       // buf_tile: 2 * buffer + tile of the stage
+        constexpr int BT = decltype(buf_tile)::value;
+        const uint4 *base = &stage[BT >> 1][(BT & 1) * LPR * 32];
+        f32x16 acc;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                const int c = 4 * s + kg;
-                a[s] = __builtin_bit_cast(bf16x8, buf[(tile * LPR + c) * 16 + (n ^ c)]);
-            }
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
-            for (int qt = 0; qt < kQueryTiles; ++qt) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < NS; ++s)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s], qreg[qt][s], acc, 0, 0, 0);
-                S[qt][kt] = acc;
-            }
-        }
+        for (int s = 0; s < NS; ++s)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, base[slot[s]]), qreg[s], acc, 0, 0, 0);
+        S = acc;
     };
-    auto absorb = [&](int u, f32x4(&S)[kQueryTiles][kStepTiles], auto masked) {
-        const int k0 = u * kStepKeys;
+    auto absorb = [&](int u, f32x16 &S, auto masked) {
+        if (masked) {                          // key k0 + 8 (v / 4) + 4 g + v % 4 against query qw0 + r
+            const int k0 = u * kStepKeys;
 #pragma unroll
-        for (int qt = 0; qt < kQueryTiles; ++qt) {
-            if (masked) {                      // key k0 + 16 kt + 4 kg + r against query qw0 + 16 qt + n
-#pragma unroll
-                for (int kt = 0; kt < kStepTiles; ++kt)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (k0 + kt * 16 + 4 * kg + r > qw0 + qt * 16 + n) S[qt][kt][r] = kMinusInf;
-            }
-            float raw = kMinusInf;
-#pragma unroll
-            for (int kt = 0; kt < kStepTiles; ++kt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) raw = max_of(raw, S[qt][kt][r]);
-            const float top = max_of(m[qt], raw * scale_log2e);   // stays finite: m starts finite
-            float sum = l[qt] * exp2_fast(m[qt] - top);
-#pragma unroll
-            for (int kt = 0; kt < kStepTiles; ++kt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) sum += exp2_fast(fmaf(S[qt][kt][r], scale_log2e, -top));
-            m[qt] = top;
-            l[qt] = sum;
+            for (int v = 0; v < 16; ++v)
+                if (k0 + 8 * (v / 4) + 4 * g + v % 4 > qw0 + r) S[v] = kMinusInf;
         }
+        float raw = kMinusInf;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) raw = max_of(raw, S[v]);
+        const float top = max_of(m, raw * scale_log2e);   // stays finite: m starts finite
+        // all exponents, then all exp2, then a tree of adds: independent instructions back to back
+        float p[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) p[v] = fmaf(S[v], scale_log2e, -top);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) p[v] = exp2_fast(p[v]);
+        const float keep = l * exp2_fast(m - top);
+#pragma unroll
+        for (int w = 8; w > 0; w >>= 1)
+#pragma unroll
+            for (int v = 0; v < w; ++v) p[v] += p[v + w];
+        m = top;
+        l = keep + p[0];
     };
-    // A step in the interior of the causal region: the maximum / sum update of its logits (`cur`)
-    // is issued together with the products of the next step (`nxt`) in one straight block, so
-    // that the vector unit and the matrix cores of a SIMD work at the same time.
-    auto plain_step = [&](int u, f32x4(&cur)[kQueryTiles][kStepTiles], f32x4(&nxt)[kQueryTiles][kStepTiles]) {
-        __builtin_amdgcn_sched_barrier(0);                          // a scheduling region of its own
-        products(u + 1, nxt);
+    // A step in the interior of the causal region: the products of the next step (`nxt`) are
+    // issued first, the maximum / sum update of this step's logits (`cur`) follows while the
+    // matrix cores work.
+    auto plain_step = [&](int u, auto next_buf_tile, f32x16 &cur, f32x16 &nxt) {
+        products(next_buf_tile, nxt);
         absorb(u, cur, std::false_type{});
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * NS, 0);     // LDS reads of the key tiles
-        __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);         // vector work while they land
-#pragma unroll
-        for (int i = 0; i < kQueryTiles * kStepTiles * NS; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one matrix instruction
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);      // three vector instructions
-            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);      // one exp2
-        }
-        __builtin_amdgcn_sched_barrier(0);
     };
+    using BT0 = std::integral_constant<int, 0>;    // buffer 0, tile 0
+    using BT1 = std::integral_constant<int, 1>;    // buffer 0, tile 1
+    using BT2 = std::integral_constant<int, 2>;    // buffer 1, tile 0
+    using BT3 = std::integral_constant<int, 3>;    // buffer 1, tile 1
 
     // Stage `diag` holds the wave's own keys (masked per element); the stages before it are
     // interior, the stages after it lie right of the diagonal and only need this wave's share of
-    // the staging.  Three loops instead of one loop with branches: no register shuffling where
-    // control flow would merge.  Every wave passes the same number of barriers.
+    // the staging.  Separate loops instead of one loop with branches: no register shuffling
+    // where control flow would merge.  Every wave passes the same number of barriers.
     const int diag = qw0 / kStageKeys;
     const bool active = diag < n_stages;               // false: the wave lies past the prompt
     const int interior = active ? diag : 0;
-    f32x4 S0[kQueryTiles][kStepTiles], S1[kQueryTiles][kStepTiles];
+    f32x16 S0, S1;
     fetch(0);
     deposit(0);
     __syncthreads();
-    if (active) products(0, S0);
-    int st = 0;
-    for (; st < interior; ++st) {
-        fetch(st + 1);                            // st + 1 <= diag < n_stages
-        plain_step(2 * st, S0, S1);
-        deposit((st + 1) & 1);
+    if (active) products(BT0{}, S0);
+    // an interior stage in buffer B: tile 1 of the stage, then (after the barrier that publishes
+    // the next stage in the other buffer) tile 0 of that one
+    auto interior_stage = [&](int st, auto buffer) {
+        constexpr int B = decltype(buffer)::value;
+        fetch(st + 1);                                  // st + 1 <= diag < n_stages
+        plain_step(2 * st, std::integral_constant<int, 2 * B + 1>{}, S0, S1);
+        deposit(B ^ 1);
         __syncthreads();
-        plain_step(2 * st + 1, S1, S0);                 // its products read the stage deposited just now
-    }
-    if (active) {
+        plain_step(2 * st + 1, std::integral_constant<int, 2 * (B ^ 1)>{}, S1, S0);
+    };
+    auto diagonal_stage = [&](int st, auto buffer) {
+        constexpr int B = decltype(buffer)::value;
         // the last stage of the workgroup fetches itself again and parks it in the idle buffer
         fetch(min(st + 1, n_stages - 1));
-        products(2 * st + 1, S1);
+        const bool second = qw0 % kStageKeys != 0;      // else the stage's second tile lies right of every query
+        if (second) products(std::integral_constant<int, 2 * B + 1>{}, S1);
         absorb(2 * st, S0, std::true_type{});
-        deposit((st + 1) & 1);
+        deposit(B ^ 1);
         __syncthreads();
-        absorb(2 * st + 1, S1, std::true_type{});
+        if (second) absorb(2 * st + 1, S1, std::true_type{});
+    };
+    int st = 0;
+    for (; st + 1 < interior; st += 2) {
+        interior_stage(st, BT0{});
+        interior_stage(st + 1, BT1{});
+    }
+    if (st < interior) {
+        interior_stage(st, BT0{});
+        ++st;
+        diagonal_stage(st, BT1{});
+        ++st;
+    } else if (active) {
+        diagonal_stage(st, BT0{});
         ++st;
     }
     for (; st < n_stages; ++st) {
@@ -238,22 +239,16 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
         __syncthreads();
     }
 
-    // Denominators: merge the four key groups of every query; log2 of the row sum, relative to 0.
+    // Denominator: merge the two key halves of every query; log2 of the row sum, relative to 0.
     float echo = 0.f, induction = 0.f;
-#pragma unroll
-    for (int qt = 0; qt < kQueryTiles; ++qt) {
-        float mm = m[qt], ll = l[qt];
-#pragma unroll
-        for (int o = 16; o < 64; o <<= 1) {
-            const float mo = __shfl_xor(mm, o), lo = __shfl_xor(ll, o);
-            const float top = fmaxf(mm, mo);
-            ll = ll * exp2_fast(mm - top) + lo * exp2_fast(mo - top);
-            mm = top;
-        }
-        const float lse2 = mm + __log2f(ll);
-        // Target logits: lane (kg, n) holds pieces 4 s + kg of query n and takes the same pieces
-        // of the target key; the four key groups then add up.
-        const int q = qw0 + qt * 16 + n;
+    {
+        const float mo = __shfl_xor(m, 32), lo = __shfl_xor(l, 32);
+        const float top = fmaxf(m, mo);
+        const float ll = l * exp2_fast(m - top) + lo * exp2_fast(mo - top);
+        const float lse2 = top + __log2f(ll);
+        // Target logits: lane (g, r) holds pieces 2 s + g of query r and takes the same pieces of
+        // the target key; the two halves then add up.
+        const int q = qw0 + r;
         const bool valid = q < n_tokens && q >= period;
         int prev = q - period;
         bool live = valid;
@@ -264,17 +259,14 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
                 const uint16_t *ki = ke + k_stride_n;            // prev + 1 <= q since period >= 1
 #pragma unroll
                 for (int s = 0; s < NS; ++s) {
-                    const uint4 qv = __builtin_bit_cast(uint4, qreg[qt][s]);
-                    de = dot_piece(qv, *reinterpret_cast<const uint4 *>(ke + (4 * s + kg) * 8), de);
-                    di = dot_piece(qv, *reinterpret_cast<const uint4 *>(ki + (4 * s + kg) * 8), di);
+                    const uint4 qv = __builtin_bit_cast(uint4, qreg[s]);
+                    de = dot_piece(qv, *reinterpret_cast<const uint4 *>(ke + (2 * s + g) * 8), de);
+                    di = dot_piece(qv, *reinterpret_cast<const uint4 *>(ki + (2 * s + g) * 8), di);
                 }
             }
-#pragma unroll
-            for (int o = 16; o < 64; o <<= 1) {
-                de += __shfl_xor(de, o);
-                di += __shfl_xor(di, o);
-            }
-            if (live && kg == 0) {
+            de += __shfl_xor(de, 32);
+            di += __shfl_xor(di, 32);
+            if (live && g == 0) {
                 echo += exp2_fast(fmaf(de, scale_log2e, -lse2));
                 induction += exp2_fast(fmaf(di, scale_log2e, -lse2));
             }
@@ -288,9 +280,9 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
         induction += __shfl_xor(induction, o);
     }
     if (lane == 0) {
-        float *dst = partial + (((int64_t)head * n_tiles + tile) * 4 + wave) * 2;
-        dst[0] = echo;
-        dst[1] = induction;
+        float *out = partial + (((int64_t)head * n_tiles + tile) * 4 + wave) * 2;
+        out[0] = echo;
+        out[1] = induction;
     }
 }
 
