@@ -28,6 +28,7 @@ constexpr int kStageKeys = 64;                            // keys staged in LDS 
 constexpr int kStepKeys = 32;                             // keys per pipeline step: one 32-key tile
 constexpr float kLowest = -1.0e30f;                       // finite "no key seen yet"
 constexpr float kMinusInf = -__builtin_huge_valf();
+constexpr float kRenormalise = 0x1p100f;                  // running sums above this are rebased on the maximum
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 // max(a, b) as the median of (a, b, +inf): no NaN quieting of the operands, and the compiler
@@ -149,7 +150,8 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, base[slot[s]]), qreg[s], acc, 0, 0, 0);
         S = acc;
     };
-    auto absorb = [&](int u, f32x16 &S, auto masked) {
+    // Exact update: m becomes the maximum of everything seen, l the sum relative to it.
+    auto absorb_exact = [&](int u, f32x16 &S, float l_before, auto masked) {
         if (masked) {                          // key k0 + 8 (v / 4) + 4 g + v % 4 against query qw0 + r
             const int k0 = u * kStepKeys;
 #pragma unroll
@@ -166,7 +168,7 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
         for (int v = 0; v < 16; ++v) p[v] = fmaf(S[v], scale_log2e, -top);
 #pragma unroll
         for (int v = 0; v < 16; ++v) p[v] = exp2_fast(p[v]);
-        const float keep = l * exp2_fast(m - top);
+        const float keep = l_before * exp2_fast(m - top);
 #pragma unroll
         for (int w = 8; w > 0; w >>= 1)
 #pragma unroll
@@ -174,12 +176,31 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
         m = top;
         l = keep + p[0];
     };
+    // Interior update.  m only has to be some logit already seen (a reference point, not the
+    // maximum) as long as the sum stays inside the fp32 range: the exponents are taken against
+    // the old m right away and the maximum is computed only on the rare step where the sum
+    // passes 2^100 or overflows (the very first step, where m is still the start value, is one).
+    // Terms that underflow against m are below 2^-126 of a term already in the sum.
+    auto absorb_fast = [&](int u, f32x16 &S) {
+        float p[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) p[v] = fmaf(S[v], scale_log2e, -m);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) p[v] = exp2_fast(p[v]);
+#pragma unroll
+        for (int w = 8; w > 0; w >>= 1)
+#pragma unroll
+            for (int v = 0; v < w; ++v) p[v] += p[v + w];
+        const float l_before = l;
+        l = l_before + p[0];
+        if (__any(!(l < kRenormalise))) absorb_exact(u, S, l_before, std::false_type{});
+    };
     // A step in the interior of the causal region: the products of the next step (`nxt`) are
     // issued first, the maximum / sum update of this step's logits (`cur`) follows while the
     // matrix cores work.
     auto plain_step = [&](int u, auto next_buf_tile, f32x16 &cur, f32x16 &nxt) {
         products(next_buf_tile, nxt);
-        absorb(u, cur, std::false_type{});
+        absorb_fast(u, cur);
     };
     using BT0 = std::integral_constant<int, 0>;    // buffer 0, tile 0
     using BT1 = std::integral_constant<int, 1>;    // buffer 0, tile 1
@@ -214,10 +235,10 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
         fetch(min(st + 1, n_stages - 1));
         const bool second = qw0 % kStageKeys != 0;      // else the stage's second tile lies right of every query
         if (second) products(std::integral_constant<int, 2 * B + 1>{}, S1);
-        absorb(2 * st, S0, std::true_type{});
+        absorb_exact(2 * st, S0, l, std::true_type{});
         deposit(B ^ 1);
         __syncthreads();
-        if (second) absorb(2 * st + 1, S1, std::true_type{});
+        if (second) absorb_exact(2 * st + 1, S1, l, std::true_type{});
     };
     int st = 0;
     for (; st + 1 < interior; st += 2) {
@@ -286,21 +307,29 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
     }
 }
 
-// Adds a head's per-wave sums in index order (double) and divides by the number of scored rows.
-__global__ void head_scores_reduce_kernel(const float *__restrict__ partial, int n_heads, int per_head,
-                                          double inv_rows, float *__restrict__ echo,
-                                          float *__restrict__ induction)
+// One wavefront per head: lane i adds the per-wave sums i, i + 64, ... in double, then the lanes
+// are folded in a fixed butterfly; divides by the number of scored rows.
+__global__ __launch_bounds__(64) void head_scores_reduce_kernel(const float *__restrict__ partial, int per_head,
+                                                                double inv_rows, float *__restrict__ echo,
+                                                                float *__restrict__ induction)
 {
-    const int head = blockIdx.x * blockDim.x + threadIdx.x;
-    if (head >= n_heads) return;
-    const float *src = partial + (int64_t)head * per_head * 2;
+    const int head = blockIdx.x, lane = threadIdx.x;
+    const float2 *src = reinterpret_cast<const float2 *>(partial) + (int64_t)head * per_head;
     double e = 0.0, i = 0.0;
-    for (int k = 0; k < per_head; ++k) {
-        e += (double)src[2 * k];
-        i += (double)src[2 * k + 1];
+    for (int k = lane; k < per_head; k += 64) {
+        const float2 v = src[k];
+        e += (double)v.x;
+        i += (double)v.y;
     }
-    echo[head] = (float)(e * inv_rows);
-    induction[head] = (float)(i * inv_rows);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        e += __shfl_xor(e, o);
+        i += __shfl_xor(i, o);
+    }
+    if (lane == 0) {
+        echo[head] = (float)(e * inv_rows);
+        induction[head] = (float)(i * inv_rows);
+    }
 }
 
 }  // namespace
@@ -347,8 +376,8 @@ extern "C" int razor_head_scores(const void *Q, const void *K, int dtype, int n_
         hipLaunchKernelGGL((head_scores_kernel<64>), grid, dim3(256), 0, s, q, k, q_stride_h, q_stride_n,
                            k_stride_h, k_stride_n, n_tokens, n_q_heads / n_kv_heads, period, all_copies,
                            scale_log2e, n_tiles, partial);
-    hipLaunchKernelGGL(head_scores_reduce_kernel, dim3((n_q_heads + 255) / 256), dim3(256), 0, s, partial,
-                       n_q_heads, n_tiles * 4, 1.0 / (double)(n_tokens - period), echo, induction);
+    hipLaunchKernelGGL(head_scores_reduce_kernel, dim3(n_q_heads), dim3(64), 0, s, partial, n_tiles * 4,
+                       1.0 / (double)(n_tokens - period), echo, induction);
     const hipError_t err = hipGetLastError();
     if (err != hipSuccess) return hip_failure("razor_head_scores launch", (int)err);
     return RAZOR_OK;

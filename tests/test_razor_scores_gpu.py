@@ -60,6 +60,24 @@ def test_scores_parity_on_unstructured_and_peaked_inputs():
         check(Q, K, d ** -0.5, 161, True, f"d={d} gain={gain} all copies")
 
 
+@pytest.mark.parametrize("log2_per_key", [0.25, 1.0, 5.0, -1.0])
+def test_scores_with_steadily_climbing_logits(log2_per_key):
+    """Logits that rise by a fixed amount per key: the running sum of an interior step passes any
+    fixed range again and again (at 5 units per key every 32-key step overflows fp32 against the
+    previous reference), so the denominators only come out right if every rebasing does.  With
+    period 1 the two targets are the newest key and the one before it, whose weights are not small."""
+    say(f"head scores: logits climbing {log2_per_key} log2 units per key")
+    N, d = 700, 128
+    u = torch.zeros(d); u[3] = 1.0
+    ramp = torch.arange(N, dtype=torch.float32) * (log2_per_key * np.log(2.0))
+    g = torch.Generator().manual_seed(11)
+    K = (0.05 * torch.randn(1, N, d, generator=g) + ramp[None, :, None] * u).to(torch.bfloat16).to(DEV)
+    Q = (0.05 * torch.randn(2, N, d, generator=g) + u).to(torch.bfloat16).to(DEV)
+    e, i, re, ri = check(Q, K, 1.0, 1, False, f"ramp {log2_per_key}")
+    if log2_per_key > 0:
+        assert (ri > 0.1).all() and (re > 0.01).all()        # the comparison above was not about zeros
+
+
 def test_scores_one_hot_prompt_closed_form():
     """The constructed prompt of the oracle's pins, on the GPU: logit beta on matching keys."""
     say("head scores: one-hot prompt")
