@@ -35,6 +35,13 @@ __device__ __forceinline__ uint4 stream_load16(const char *p)
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
+// The arena rows written here are next read by the first decode step, long after they have left
+// the caches: store them non-temporally (measured on a plain copy: 6.2 against 5.7 TB/s).
+__device__ __forceinline__ void stream_store16(char *p, const uint4 v)
+{
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
+}
+
 // Adds the elements of one 16-byte piece to acc[0..NE).
 template <int DTYPE>
 __device__ __forceinline__ void accumulate_piece(const uint4 &v, float *acc)
@@ -236,7 +243,7 @@ __global__ __launch_bounds__(256) void compact_kernel(
 #pragma unroll
     for (int r = 0; r < NI; ++r) {
         const int row = r * RPI + prow;
-        *reinterpret_cast<uint4 *>(vplane + (int64_t)(blk * kBlockRows + row) * RB + piece * 16) = vv[r];
+        stream_store16(vplane + (int64_t)(blk * kBlockRows + row) * RB + piece * 16, vv[r]);
         stage[wave][row * LPR + (piece ^ (row % LPR))] = kv[r];   // xor: conflict-free column reads
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -247,7 +254,7 @@ __global__ __launch_bounds__(256) void compact_kernel(
     for (int s = 0; s < NI; ++s) {
         const int pos = s * 64 + lane;                // 16-byte slot inside the block
         const int c = pos / 16, r = pos % 16;         // piece-major: slot = c * 16 + r
-        *reinterpret_cast<uint4 *>(kblock + (int64_t)pos * 16) = stage[wave][r * LPR + (c ^ (r % LPR))];
+        stream_store16(kblock + (int64_t)pos * 16, stage[wave][r * LPR + (c ^ (r % LPR))]);
     }
 }
 
