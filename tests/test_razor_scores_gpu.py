@@ -40,6 +40,10 @@ def check(Q, K, scale, period, all_copies, what):
     (2, 2, 64, 37, 200),          # a single tile, five and a half repeats
     (6, 3, 128, 256, 1024),       # everything aligned to the tile sizes
     (3, 3, 64, 1, 130),           # period 1: the induction token is the current one
+    (1, 1, 64, 1, 2),             # the smallest prompt there is: one scored row
+    (2, 1, 128, 7, 33),           # one wave and one row of the next
+    (2, 2, 64, 64, 65),           # one scored row, the first of the second stage
+    (2, 2, 128, 5, 129),          # one row into the second workgroup
 ])
 @pytest.mark.parametrize("all_copies", [False, True])
 def test_scores_parity(hq, hkv, d, period, n_tokens, all_copies):
