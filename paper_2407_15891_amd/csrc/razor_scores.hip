@@ -55,8 +55,8 @@ __device__ __forceinline__ float dot_piece(const uint4 a, const uint4 b, float a
 // the banks, and a wave still reads one contiguous kilobyte per matrix-core operand).
 //   S^T[key][query] = K[key][:] . Q[query][:]   v_mfma_f32_32x32x16_bf16, A = key tile, B = Q
 //   lane (g, r) gets query r of the wave and, in accumulator register v, key
-//   8 (v / 4) + 4 g + v % 4 of the tile: the running maximum and sum of a query stay inside a
-//   lane until the two key halves are merged at the very end.
+//   8 (v / 4) + 4 g + v % 4 of the tile: the running reference and sum of a query stay inside
+//   a lane until the two key halves are merged at the very end.
 // The 32x32 shape halves the matrix instructions per logit against 16x16x32; what bounds this
 // kernel is the vector unit (one fma, one exp2, one add per logit), and every matrix
 // instruction costs it about two issue slots whatever its size.
@@ -94,7 +94,8 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
                 bf16x8, *reinterpret_cast<const uint4 *>(Qh + (int64_t)row * q_stride_n + (2 * s + g) * 8));
     }
 
-    // running maximum (already times scale * log2 e) and sum of 2^(logit - maximum)
+    // reference point (a scaled logit already seen, or the start value) and the sum of
+    // 2^(scale * log2 e * logit - reference) over the keys absorbed so far
     float m = kLowest, l = 0.f;
 
     const int n_stages = (min(q0 + kQueriesPerGroup, n_tokens) + kStageKeys - 1) / kStageKeys;
