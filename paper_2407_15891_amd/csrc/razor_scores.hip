@@ -100,18 +100,33 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
 
     const int n_stages = (min(q0 + kQueriesPerGroup, n_tokens) + kStageKeys - 1) / kStageKeys;
     static_assert(LOADS == 2 || LOADS == 4, "a thread moves two or four pieces per stage");
-    // Staging: thread t moves pieces t, t + 256, ... of a stage (row-major, coalesced).  The
-    // source pointers advance by one stage per step; rows past the prompt read its last row.
-    // Piece j of a thread sits 256 / LPR rows below piece j - 1, in the same column: one pointer,
-    // one row number and one LDS slot per thread, the rest are constant offsets.
+    // Staging: thread t moves pieces t, t + 256, ... of a stage (row-major, coalesced); piece j
+    // of a thread sits 256 / LPR rows below piece j - 1, in the same column.  Per thread: one
+    // running source pointer (advanced by a stage per fetch), and the LDS slots of its pieces.
     constexpr int ROWS_PER_LOAD = 256 / LPR;
     const int64_t stage_elems = (int64_t)kStageKeys * k_stride_n;
     const int64_t load_elems = (int64_t)ROWS_PER_LOAD * k_stride_n;
     const int row0 = (int)threadIdx.x / LPR, col = (int)threadIdx.x % LPR;
-    const uint16_t *src = Kh + (int64_t)row0 * k_stride_n + col * 8;
-    const uint16_t *tail = Kh + (int64_t)last * k_stride_n + col * 8;
-    auto slot_of = [&](int row) { return ((row >> 5) * LPR + col) * 32 + ((row & 31) ^ col); };
+    const uint16_t *src = Kh + (int64_t)row0 * k_stride_n + col * 8;     // this thread's first piece of stage 0
+    const uint16_t *tail = Kh + (int64_t)last * k_stride_n + col * 8;    // same column of the last row
+    int slot_of[LOADS];
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+        const int row = row0 + j * ROWS_PER_LOAD;
+        slot_of[j] = ((row >> 5) * LPR + col) * 32 + ((row & 31) ^ col);
+    }
     uint4 hold0, hold1, hold2 = {}, hold3 = {};   // named registers: they stay in registers across the barrier
+    // a stage that ends inside the prompt: no row needs clamping
+    auto fetch_inside = [&](int st) {
+        const uint16_t *from = src + st * stage_elems;
+        hold0 = *reinterpret_cast<const uint4 *>(from);
+        hold1 = *reinterpret_cast<const uint4 *>(from + load_elems);
+        if constexpr (LOADS == 4) {
+            hold2 = *reinterpret_cast<const uint4 *>(from + 2 * load_elems);
+            hold3 = *reinterpret_cast<const uint4 *>(from + 3 * load_elems);
+        }
+    };
+    // any stage: rows past the prompt read its last row
     auto fetch_piece = [&](int st, int j) {
         const uint16_t *from = st * kStageKeys + row0 + j * ROWS_PER_LOAD > last ? tail
                                                                                   : src + st * stage_elems + j * load_elems;
@@ -126,11 +141,12 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
         }
     };
     auto deposit = [&](int buf) {
-        stage[buf][slot_of(row0)] = hold0;
-        stage[buf][slot_of(row0 + ROWS_PER_LOAD)] = hold1;
+        uint4 *to = stage[buf];
+        to[slot_of[0]] = hold0;
+        to[slot_of[1]] = hold1;
         if constexpr (LOADS == 4) {
-            stage[buf][slot_of(row0 + 2 * ROWS_PER_LOAD)] = hold2;
-            stage[buf][slot_of(row0 + 3 * ROWS_PER_LOAD)] = hold3;
+            to[slot_of[2]] = hold2;
+            to[slot_of[3]] = hold3;
         }
     };
 
@@ -222,9 +238,10 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
     if (active) products(BT0{}, S0);
     // an interior stage in buffer B: tile 1 of the stage, then (after the barrier that publishes
     // the next stage in the other buffer) tile 0 of that one
-    auto interior_stage = [&](int st, auto buffer) {
+    auto interior_stage = [&](int st, auto buffer, auto next_inside) {
         constexpr int B = decltype(buffer)::value;
-        fetch(st + 1);                                  // st + 1 <= diag < n_stages
+        if (next_inside) fetch_inside(st + 1);          // st + 1 <= diag < n_stages
+        else fetch(st + 1);
         plain_step(2 * st, std::integral_constant<int, 2 * B + 1>{}, S0, S1);
         deposit(B ^ 1);
         __syncthreads();
@@ -241,18 +258,25 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
         __syncthreads();
         if (second) absorb_exact(2 * st + 1, S1, l, std::true_type{});
     };
+    // Every stage but the workgroup's last one ends inside the prompt and is fetched without
+    // clamping; that covers all interior stages except possibly a wave's last one.
+    const int unclamped = min(interior, n_stages - 2);  // stages st < unclamped have st + 1 <= n_stages - 2
     int st = 0;
-    for (; st + 1 < interior; st += 2) {
-        interior_stage(st, BT0{});
-        interior_stage(st + 1, BT1{});
+    for (; st + 1 < unclamped; st += 2) {
+        interior_stage(st, BT0{}, std::true_type{});
+        interior_stage(st + 1, BT1{}, std::true_type{});
     }
-    if (st < interior) {
-        interior_stage(st, BT0{});
+    if (st < interior) {                                // at most two interior stages are left
+        interior_stage(st, BT0{}, std::false_type{});
         ++st;
-        diagonal_stage(st, BT1{});
-        ++st;
-    } else if (active) {
-        diagonal_stage(st, BT0{});
+        if (st < interior) {
+            interior_stage(st, BT1{}, std::false_type{});
+            ++st;
+        }
+    }
+    if (active) {
+        if (st & 1) diagonal_stage(st, BT1{});
+        else diagonal_stage(st, BT0{});
         ++st;
     }
     for (; st < n_stages; ++st) {
