@@ -44,7 +44,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 #define RAZOR_STAMP_SEG() ++stamp_segments
 #define RAZOR_STAMP_FLUSH()                                                                        \
     if (lane == 0) {                                                                               \
-        long long *dst = reinterpret_cast<long long *>(part_acc + (size_t)7000 * g * (RB / 2)) + (size_t)w * 4; \
+        long long *dst = reinterpret_cast<long long *>(part_acc + (size_t)7000 * g * D) + (size_t)w * 4;        \
         dst[0] = stamp_0; dst[1] = stamp_1; dst[2] = stamp_2; dst[3] = stamp_segments;             \
     }
 #else
@@ -369,14 +369,25 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
     RAZOR_STAMP_FLUSH();
 }
 
-// ---------------------------------------------------------------- partial, fp32 / vector ALU
+// ---------------------------------------------------------------- partial, fp32 / matrix cores
 //
-// Lane l = 16 * kg + n holds, per K load s, the 4 floats of piece 4*s + kg of row n; the
-// dot product is finished across the four kg groups with two shuffles.  V is read
-// row-major: lane (prow, piece) holds 4 columns of row i*RPI + prow and picks that row's
-// probability from the lane that owns it.
-template <int D, int G, int PF>
-__global__ __launch_bounds__(256) void decode_partial_f32_kernel(
+// Same scheme as the bf16 kernel with v_mfma_f32_16x16x4_f32 (one float of A and of B per lane,
+// contraction length 4).  Lane l = 16 * kg + n.  For one 16-row block:
+//   S[row][head] = K[row][:] . Q[head][:]   lane (kg, n) loads 16 bytes = columns
+//                  16 s + 4 kg .. + 3 of row n (the piece-major K plane makes that one contiguous
+//                  kilobyte per load) and feeds them to four products in turn, against the same
+//                  four columns of query n; the order of the contraction is immaterial as long as
+//                  A and B agree.  The lane ends up with head n, rows 4 kg .. 4 kg + 3.
+//   O^T[col][head] += V^T[col][row] . P[row][head]   lane (kg, n) loads columns 64 q + 4 n .. + 3
+//                  of rows 4 kg .. 4 kg + 3 (coalesced: 256 contiguous bytes per row), one product
+//                  per loaded element and row; its exp2 values are already the B operand.
+//                  Accumulator (q, e) of lane (kg, n) holds head n, columns 64 q + 16 kg + 4 j + e.
+// 64 matrix instructions per 16-row block (D = 128) at 32 cycles each: about half of the time the
+// block's 16 KB take to arrive at this SIMD's share of the HBM rate.  Two blocks in flight, the
+// query group of this head and of the next and the accumulators need more than 256 registers:
+// one wavefront per SIMD, which is how the kernel is launched anyway.
+template <int D, int PF>
+__global__ __launch_bounds__(256, 1) void decode_partial_f32_kernel(
     const float *__restrict__ Q, char *__restrict__ arena,
     const razor_head_desc *__restrict__ desc, const char *__restrict__ k_new,
     const char *__restrict__ v_new, float *__restrict__ comp, int32_t *__restrict__ prefix,
@@ -384,17 +395,14 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
     int n_heads, int n_kv_heads, int g, int n_workers, int sliding, int n_sink,
     const float *__restrict__ slopes, float scale_log2e)
 {
-    constexpr int RB = D * 4;
-    constexpr int NS = RB / 64;     // K loads per block
-    constexpr int LPR = RB / 16;    // lanes per V row
-    constexpr int RPI = 64 / LPR;   // V rows per load
-    constexpr int NI = 16 / RPI;    // V loads per block
-    __shared__ float qs[4][G * D];  // the query group, private to each wave
+    constexpr int RB = D * 4;     // bytes per row
+    constexpr int NS = D / 16;    // K loads per block, four first-product steps each
+    constexpr int VQ = D / 64;    // V loads per lane per row
+    constexpr int VE = 4 * VQ;    // V elements per lane per row = accumulators
 
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int w = blockIdx.x * 4 + wave;
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int kg = lane >> 4, n = lane & 15;
-    const int prow = lane / LPR, piece = lane % LPR;
     const int has_new = k_new != nullptr;
 #ifdef RAZOR_TIMELINE
     long long stamp_segments = 0;
@@ -410,17 +418,32 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
     if (lo >= hi) return;
     RAZOR_STAMP(1);
 
-    while (lo < hi) {
-        razor_head_desc e = desc[i];
-        int rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
-        while (first + (rows + kBlockRows - 1) / kBlockRows <= lo) {   // heads without a block here
-            first += (rows + kBlockRows - 1) / kBlockRows;
-            e = desc[++i];
-            rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
+    // The query group of head `head` as B operand of the first product (zero rows pad the group).
+    auto load_query = [&](int head, f32x4(&q)[NS]) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            q[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (n < g) q[s] = *reinterpret_cast<const f32x4 *>(Q + ((int64_t)head * g + n) * D + (4 * s + kg) * 4);
         }
+    };
+    razor_head_desc e = desc[i];   // head i owns block lo (locate_block never returns an empty head)
+    f32x4 qreg[NS];
+    load_query(i, qreg);
+
+    while (lo < hi) {
+        const int rows = count.rows_of(e.rows, e.cap, e.flags, e.window);
         const int head_end = first + (rows + kBlockRows - 1) / kBlockRows;
         const int seg_end = hi < head_end ? hi : head_end;
-        const int b = i / n_kv_heads, h = i % n_kv_heads;
+        // A range that runs past this head continues in the next one: fetch that head's entry and
+        // query group now, so that the switch does not wait for them.
+        const bool more = seg_end < hi;
+        razor_head_desc e_next = e;
+        f32x4 q_next[NS];
+        if (more) {
+            e_next = desc[i + 1];
+            load_query(i + 1, q_next);
+        }
+        const int h = i % n_kv_heads;
         char *kplane = arena + e.row_off * 2 * RB;
         char *vplane = kplane + (int64_t)e.cap * RB;
         if (has_new) {   // the wave that owns the block of the row the new token goes to stores it
@@ -432,73 +455,77 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
             }
         }
 
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        for (int t = lane; t < G * D; t += 64)
-            qs[wave][t] = t < g * D ? Q[(int64_t)(b * n_kv_heads + h) * g * D + t] : 0.f;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
         const bool slides_now = count.slides(e.rows, e.flags, e.window);
         const RowDistance distance(e, rows, slides_now, n_sink);
+        const float slope_l2e = (slopes && n < g) ? slopes[h * g + n] * 1.4426950408889634f : 0.f;
 
-        float m[G], l[G];
-        float4 acc[G];
+        float m = kNegInf, l = 0.f;
+        f32x4 acc[VE];
 #pragma unroll
-        for (int j = 0; j < G; ++j) {
-            m[j] = kNegInf;
-            l[j] = 0.f;
-            acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        for (int c = 0; c < VE; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        f32x4 kb[PF][NS], vb[PF][NI];
-        auto load_block = [&](int t, f32x4(&k)[NS], f32x4(&v)[NI]) {
+        f32x4 kb[PF][NS], vb[PF][4][VQ];
+        auto load_block = [&](int t, f32x4(&k)[NS], f32x4(&v)[4][VQ]) {
             const f32x4 *kp = reinterpret_cast<const f32x4 *>(kplane + (int64_t)t * kBlockRows * RB) + lane;
 #pragma unroll
             for (int s = 0; s < NS; ++s) k[s] = stream_load(kp + s * 64);
 #pragma unroll
-            for (int r = 0; r < NI; ++r) {
-                int row = t * kBlockRows + r * RPI + prow;
-                row = row < rows ? row : rows - 1;
-                v[r] = stream_load(reinterpret_cast<const f32x4 *>(vplane + (int64_t)row * RB) + piece);
+            for (int r = 0; r < 4; ++r) {
+                int row = t * kBlockRows + 4 * kg + r;
+                row = row < rows ? row : rows - 1;   // stay on initialised, finite rows
+#pragma unroll
+                for (int q = 0; q < VQ; ++q)
+                    v[r][q] = stream_load(reinterpret_cast<const f32x4 *>(vplane + (int64_t)row * RB) + 16 * q + n);
             }
         };
-        auto compute_block = [&](int t, const f32x4(&k)[NS], const f32x4(&v)[NI]) {
-            const bool valid = t * kBlockRows + n < rows;
+        auto compute_block = [&](int t, const f32x4(&k)[NS], const f32x4(&v)[4][VQ]) {
+            f32x4 S = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < G; ++j) {
-                if (j < g) {
-                    float dot = 0.f;
+            for (int s = 0; s < NS; ++s)
 #pragma unroll
-                    for (int s = 0; s < NS; ++s) {
-                        const float4 q4 = *reinterpret_cast<const float4 *>(&qs[wave][j * D + 4 * (4 * s + kg)]);
-                        dot += k[s].x * q4.x + k[s].y * q4.y + k[s].z * q4.z + k[s].w * q4.w;
-                    }
-                    dot += __shfl_xor(dot, 16);
-                    dot += __shfl_xor(dot, 32);
-                    float sv = valid ? dot * scale_log2e : kNegInf;
-                    if (slopes) sv -= slopes[h * g + j] * 1.4426950408889634f * distance(t * kBlockRows + n);
-                    float bmax = sv;
-                    bmax = fmaxf(bmax, __shfl_xor(bmax, 1));
-                    bmax = fmaxf(bmax, __shfl_xor(bmax, 2));
-                    bmax = fmaxf(bmax, __shfl_xor(bmax, 4));
-                    bmax = fmaxf(bmax, __shfl_xor(bmax, 8));
-                    const float m_new = fmaxf(m[j], bmax);
-                    const float alpha = fast_exp2(m[j] - m_new);
-                    m[j] = m_new;
-                    const float p = fast_exp2(sv - m_new);
-                    l[j] = l[j] * alpha + p;
-                    float4 a = acc[j];
-                    a.x *= alpha; a.y *= alpha; a.z *= alpha; a.w *= alpha;
+                for (int j = 0; j < 4; ++j) S = __builtin_amdgcn_mfma_f32_16x16x4f32(k[s][j], qreg[s][j], S, 0, 0, 0);
+            float sv[4];
+            const int row0 = t * kBlockRows + 4 * kg;
+            float bmax = kNegInf;
 #pragma unroll
-                    for (int r = 0; r < NI; ++r) {
-                        const float pv = __shfl(p, r * RPI + prow);
-                        a.x += pv * v[r].x; a.y += pv * v[r].y; a.z += pv * v[r].z; a.w += pv * v[r].w;
-                    }
-                    acc[j] = a;
+            for (int r = 0; r < 4; ++r) sv[r] = S[r] * scale_log2e;
+            if (slopes) {   // Eq.(1): minus slope * distance to the query
+                int A;
+                if (distance.linear(t, A)) {
+                    const float c0 = slope_l2e * (float)(A - row0);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sv[r] -= c0 - slope_l2e * (float)r;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sv[r] -= slope_l2e * distance(row0 + r);
                 }
             }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                sv[r] = row0 + r < rows ? sv[r] : kNegInf;
+                bmax = fmaxf(bmax, sv[r]);
+            }
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+            const float m_new = fmaxf(m, bmax);     // finite: every block holds a valid row
+            const float alpha = fast_exp2(m - m_new);
+            m = m_new;
+            float pr[4], psum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                pr[r] = fast_exp2(sv[r] - m_new);
+                psum += pr[r];
+            }
+            l = l * alpha + psum;
+#pragma unroll
+            for (int q = 0; q < VQ; ++q)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    f32x4 o = acc[4 * q + c] * alpha;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o = __builtin_amdgcn_mfma_f32_16x16x4f32(v[r][q][c], pr[r], o, 0, 0, 0);
+                    acc[4 * q + c] = o;
+                }
         };
 
         const int t0 = lo - first, t1 = seg_end - first;
@@ -515,32 +542,35 @@ __global__ __launch_bounds__(256) void decode_partial_f32_kernel(
             }
         }
 
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (n < g) {
+            const size_t slot = (size_t)(w + i) * g + n;
+            float *pa = part_acc + slot * D + 16 * kg;
 #pragma unroll
-        for (int j = 0; j < G; ++j) {
-            if (j < g) {
-                float lt = l[j];   // one copy per row lives in each kg group: add over n only
-                lt += __shfl_xor(lt, 1);
-                lt += __shfl_xor(lt, 2);
-                lt += __shfl_xor(lt, 4);
-                lt += __shfl_xor(lt, 8);
-                float4 a = acc[j];
+            for (int q = 0; q < VQ; ++q)
 #pragma unroll
-                for (int o = LPR; o < 64; o <<= 1) {
-                    a.x += __shfl_xor(a.x, o);
-                    a.y += __shfl_xor(a.y, o);
-                    a.z += __shfl_xor(a.z, o);
-                    a.w += __shfl_xor(a.w, o);
-                }
-                const size_t slot = (size_t)(w + i) * g + j;
-                if (prow == 0) *reinterpret_cast<float4 *>(part_acc + slot * D + 4 * piece) = a;
-                if (lane == 0) {
-                    part_ml[slot * 2] = m[j];
-                    part_ml[slot * 2 + 1] = lt;
-                }
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<float4 *>(pa + 64 * q + 4 * j) =
+                        make_float4(acc[4 * q][j], acc[4 * q + 1][j], acc[4 * q + 2][j], acc[4 * q + 3][j]);
+            if (kg == 0) {
+                part_ml[slot * 2] = m;
+                part_ml[slot * 2 + 1] = l;
             }
         }
         lo = seg_end;
         RAZOR_STAMP_SEG();
+        if (more) {
+            first = head_end;
+            e = e_next;
+            ++i;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) qreg[s] = q_next[s];
+            while (count.rows_of(e.rows, e.cap, e.flags, e.window) == 0) {   // heads that hold no row
+                e = desc[++i];
+                load_query(i, qreg);
+            }
+        }
     }
     RAZOR_STAMP(2);
     RAZOR_STAMP_FLUSH();
@@ -674,22 +704,6 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
 
 thread_local hipEvent_t g_profile_start = nullptr, g_profile_stop = nullptr;
 
-template <int G>
-void launch_partial_f32(int D, dim3 grid, hipStream_t s, const float *Q, char *arena,
-                        const razor_head_desc *desc, const char *kn, const char *vn, float *comp,
-                        int32_t *prefix, int32_t *nd, float *ml, float *acc, int n_heads, int n_kv,
-                        int g, int workers, int sliding, int n_sink, const float *slopes, float sl2e)
-{
-    if (D == 64)
-        hipLaunchKernelGGL((decode_partial_f32_kernel<64, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
-                           kn, vn, comp, prefix, nd, ml, acc, n_heads, n_kv, g, workers, sliding, n_sink,
-                           slopes, sl2e);
-    else
-        hipLaunchKernelGGL((decode_partial_f32_kernel<128, G, 2>), grid, dim3(256), 0, s, Q, arena, desc,
-                           kn, vn, comp, prefix, nd, ml, acc, n_heads, n_kv, g, workers, sliding, n_sink,
-                           slopes, sl2e);
-}
-
 }  // namespace
 }  // namespace razor
 
@@ -741,13 +755,14 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
                                p->sliding, p->n_sink, p->alibi_slopes, sl2e);
     } else {
         const float *q = static_cast<const float *>(Q);
-#define RAZOR_F32_ARGS D, grid, s, q, a, desc_dev, kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers, p->sliding, p->n_sink, p->alibi_slopes, sl2e
-        if (g == 1) launch_partial_f32<1>(RAZOR_F32_ARGS);
-        else if (g == 2) launch_partial_f32<2>(RAZOR_F32_ARGS);
-        else if (g <= 4) launch_partial_f32<4>(RAZOR_F32_ARGS);
-        else if (g <= 8) launch_partial_f32<8>(RAZOR_F32_ARGS);
-        else launch_partial_f32<16>(RAZOR_F32_ARGS);
-#undef RAZOR_F32_ARGS
+        if (D == 128)
+            hipLaunchKernelGGL((decode_partial_f32_kernel<128, 2>), grid, dim3(256), 0, s, q, a, desc_dev,
+                               kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers,
+                               p->sliding, p->n_sink, p->alibi_slopes, sl2e);
+        else
+            hipLaunchKernelGGL((decode_partial_f32_kernel<64, 2>), grid, dim3(256), 0, s, q, a, desc_dev,
+                               kn, vn, comp, prefix, nd, ml, acc, n_heads, p->n_kv_heads, g, workers,
+                               p->sliding, p->n_sink, p->alibi_slopes, sl2e);
     }
     if (g_profile_stop) RAZOR_HIP_CHECK(hipEventRecord(g_profile_stop, s));
 

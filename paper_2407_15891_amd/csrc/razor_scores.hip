@@ -219,10 +219,8 @@ __global__ __launch_bounds__(256, 3) void head_scores_kernel(
         products(next_buf_tile, nxt);
         absorb_fast(u, cur);
     };
-    using BT0 = std::integral_constant<int, 0>;    // buffer 0, tile 0
-    using BT1 = std::integral_constant<int, 1>;    // buffer 0, tile 1
-    using BT2 = std::integral_constant<int, 2>;    // buffer 1, tile 0
-    using BT3 = std::integral_constant<int, 3>;    // buffer 1, tile 1
+    using BT0 = std::integral_constant<int, 0>;    // as argument of products: buffer 0, tile 0;
+    using BT1 = std::integral_constant<int, 1>;    // as argument of the stage lambdas: buffer 0 / 1
 
     // Stage `diag` holds the wave's own keys (masked per element); the stages before it are
     // interior, the stages after it lie right of the diagonal and only need this wave's share of
