@@ -16,8 +16,8 @@
 //             in the compensation token with weight N_d (logit + ln N_d), normalises,
 //             and makes the append permanent (rows += 1).
 //
-// bf16 caches use the matrix cores for both products (the query group is padded to
-// the 16-wide operand); fp32 caches use vector FMAs.
+// Both products run on the matrix cores (the query group is padded to the 16-wide
+// operand): v_mfma_f32_16x16x32_bf16 for bf16 caches, v_mfma_f32_16x16x4_f32 for fp32.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
