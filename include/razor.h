@@ -241,6 +241,18 @@ RAZOR_API int razor_select_heads(const float *echo_host, const float *induction_
  */
 RAZOR_API int razor_profile_events(void *ev_start, void *ev_stop);
 
+/*
+ * Measurement hook: the read-stream ceiling.  Reads the first bytes / 4096 * 4096 bytes at buf
+ * (device, 16-byte aligned, at least 4096 bytes) exactly once with the access pattern of the
+ * streaming kernels -- one contiguous range per wavefront, 128-bit non-temporal loads -- and
+ * does no other work, so the duration of this launch is what the device gives a kernel that only
+ * reads.  n_workers: 0 = four wavefronts per compute unit, as in the parameter block.  sink: device,
+ * at least 4 * RAZOR_MAX_WORKERS bytes, may be written (it keeps the loads alive).  Enqueued on
+ * `stream`; time it with events.
+ */
+RAZOR_API int razor_probe_read_stream(const void *buf, size_t bytes, int n_workers, void *sink,
+                            void *stream);
+
 /* Text for a razor_status; for RAZOR_EHIP the text of the last HIP error seen by the
  * calling thread.  The pointer stays valid until the thread's next failing call. */
 RAZOR_API const char *razor_strerror(int status);

@@ -1,8 +1,8 @@
 """Python binding of the razor C-ABI library (RazorAttention hot path on MI355X).
 
 The functions `razor_plan`, `razor_compress`, `razor_column_sums`, `razor_decode_attn`,
-`razor_head_scores`, `razor_head_scores_workspace`, `razor_select_heads`, `razor_profile_events`
-and `razor_strerror` carry the names and the argument order of `include/razor.h`; they only marshal
+`razor_head_scores`, `razor_head_scores_workspace`, `razor_select_heads`, `razor_profile_events`,
+`razor_probe_read_stream` and `razor_strerror` carry the names and the argument order of `include/razor.h`; they only marshal
 arguments (torch tensors -> device pointers, numpy arrays -> host pointers).  Every
 step of the path runs in the HIP kernels of `librazor.so`; there is no Python or CPU
 fallback: a missing library raises on first use.
@@ -30,7 +30,7 @@ RAZOR_MAX_WORKERS = 8192
 
 EXPORTS = ("razor_plan", "razor_compress", "razor_column_sums", "razor_decode_attn",
            "razor_head_scores_workspace", "razor_head_scores", "razor_select_heads",
-           "razor_profile_events", "razor_strerror")
+           "razor_profile_events", "razor_probe_read_stream", "razor_strerror")
 
 
 class RazorParams(ctypes.Structure):
@@ -101,6 +101,8 @@ def load_library():
     L.razor_select_heads.argtypes = [vp, vp, ci, ci, ctypes.c_double, ctypes.c_double, vp]
     L.razor_profile_events.restype = ctypes.c_int
     L.razor_profile_events.argtypes = [vp, vp]
+    L.razor_probe_read_stream.restype = ctypes.c_int
+    L.razor_probe_read_stream.argtypes = [vp, sz, ctypes.c_int, vp, vp]
     L.razor_strerror.restype = ctypes.c_char_p
     L.razor_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -185,6 +187,12 @@ def razor_select_heads(echo_host: np.ndarray, induction_host: np.ndarray, n_head
 def razor_profile_events(ev_start, ev_stop) -> int:
     """ev_start / ev_stop: raw hipEvent_t handles (ctypes.c_void_p) or None."""
     return load_library().razor_profile_events(ev_start, ev_stop)
+
+
+def razor_probe_read_stream(buf, nbytes: int, n_workers: int, sink, stream: int = 0) -> int:
+    """buf: device tensor, or a raw device address (int) inside one."""
+    addr = buf if isinstance(buf, int) else _dev(buf)
+    return load_library().razor_probe_read_stream(addr, nbytes, n_workers, _dev(sink), stream or None)
 
 
 def _check(status: int, where: str) -> None:

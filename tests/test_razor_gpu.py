@@ -532,6 +532,16 @@ def test_many_heads():
 
 
 # ----------------------------------------------------------------- seeded random sweep
+def test_read_stream_probe_runs_on_odd_sizes():
+    """The measurement hook reads whole 4 KB pieces inside the buffer whatever the size and worker count."""
+    buf = torch.ones(5 * 4096 * 1031 + 777, dtype=torch.uint8, device=DEV)
+    sink = torch.zeros(4 * razor.RAZOR_MAX_WORKERS, dtype=torch.uint8, device=DEV)
+    for nbytes, workers in ((4096, 0), (4096 * 3 + 5, 4), (buf.numel(), 0), (buf.numel(), 1000), (buf.numel(), 8192)):
+        assert razor.razor_probe_read_stream(buf, nbytes, workers, sink) == razor.RAZOR_OK
+    torch.cuda.synchronize()
+    assert int(sink.sum()) == 0          # the sink is only written if a checksum hits one value in 2^32
+
+
 @pytest.mark.parametrize("seed", list(range(24)))
 def test_random_shapes_parity(seed):
     """Random but seeded shapes: batch, heads, group, head_dim, dtype, ragged lengths, sinks,

@@ -261,3 +261,13 @@ def test_head_scores_arguments_are_checked_before_any_gpu_work():
     assert need == 8 * 8 * 4 * 2 * 4                                  # 8 tiles of 128 queries, 4 waves, 2 sums
     assert call(ws_bytes=need - 1) == razor.RAZOR_ECAPACITY
     assert razor.razor_head_scores_workspace(0, 10) == 0
+
+
+def test_read_stream_probe_arguments_are_checked():
+    L = razor.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    assert L.razor_probe_read_stream(None, 1 << 20, 0, fake, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_read_stream(fake, 1 << 20, 0, None, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_read_stream(ctypes.c_void_p(0x1004), 1 << 20, 0, fake, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_read_stream(fake, 100, 0, fake, None) == razor.RAZOR_EINVAL        # less than one piece
+    assert L.razor_probe_read_stream(fake, 1 << 20, -3, fake, None) == razor.RAZOR_EINVAL
