@@ -300,7 +300,10 @@ class RazorCache:
         """K, V: [B, H_kv, N, d] device tensors, last dimension contiguous.  col_sums: optional
         float32 [B, H_kv, 2, d] sums over the valid rows; with it the dropped rows are not read."""
         self._check_source(K, V)
-        assert col_sums is None or (col_sums.dtype == self.torch.float32 and col_sums.is_contiguous())
+        if col_sums is not None:
+            p = self.params
+            assert col_sums.dtype == self.torch.float32 and col_sums.is_contiguous()
+            assert tuple(col_sums.shape) == (p.batch, p.n_kv_heads, 2, p.head_dim)
         _check(razor_compress(self.params, K, V, K.stride(0), K.stride(1), K.stride(2), self.seq_lens,
                               self.mask, self.arena, self.comp, self.desc_dev, self.kept_idx_dev, col_sums,
                               self.workspace, self.workspace.numel(), self._stream()), "razor_compress")
