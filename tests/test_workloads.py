@@ -49,3 +49,15 @@ def test_determinism_and_step_inputs():
     assert a.step_inputs(0, append=False)[1] is None
     assert not torch.equal(a.K, make_workload(3, "cpu", context=300, batch=2, layer=1).K)
     assert np.isclose(a.scale, 128 ** -0.5)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only: any other --gpus value ends with a message and a non-zero status
+    before anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
