@@ -152,8 +152,8 @@ RAZOR_API int razor_plan(const razor_params *p, const int32_t *seq_lens_host,
  * col_sums (float32 [batch, n_kv_heads, 2, head_dim], nullable): sums of K and of V over rows
  * [0, seq_len) of every head, e.g. accumulated by the kernel that wrote K and V during prefill
  * (or by razor_column_sums).  When given, the dropped rows are not read at all: Eq.(4) is
- * evaluated as (col_sums - sum of the kept rows) / N_d, which roughly halves the traffic of
- * this call.  The subtraction loses accuracy when N_d is tiny against the sequence length.
+ * evaluated as (col_sums - sum of the kept rows) / N_d, the kept rows being added up while
+ * they are copied, which roughly halves the traffic of this call.  The subtraction loses accuracy when N_d is tiny against the sequence length.
  */
 RAZOR_API int razor_compress(const razor_params *p, const void *K, const void *V,
                    int64_t stride_b, int64_t stride_h, int64_t stride_n,

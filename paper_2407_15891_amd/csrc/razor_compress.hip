@@ -63,8 +63,8 @@ __device__ __forceinline__ void accumulate_piece(const uint4 &v, float *acc)
     }
 }
 
-// Eq.(4), first level.  The rows to be summed (ROWS: the dropped set of every head, or the
-// kept rows of the compressed heads, or every row) form one axis of 16-row blocks, cut into
+// Eq.(4), first level.  The rows to be summed (ROWS: the dropped set of every head, or every
+// row) form one axis of 16-row blocks, cut into
 // equal ranges, one per wavefront (same scheme as the decode kernel).  A wave streams its
 // rows once -- lane (prow, piece) owns one 16-byte piece of rows prow, prow + RPI, ... of
 // every block -- keeps fp32 column sums of K and V, adds the row groups with shuffles and
@@ -160,17 +160,14 @@ __global__ __launch_bounds__(256) void mean_stream_kernel(
 // Eq.(4), second level: add the segment sums of a head (four interleaved groups, each in
 // slot order, then the groups in order; double keeps the result independent of how the rows
 // were cut).  blockDim = (2 * D, 4).
-//   kFinalMean        comp = sum / N_d                  (the streamed rows were the dropped set)
-//   kFinalComplement  comp = (col_sums - sum) / N_d     (the streamed rows were the kept ones and
-//                     col_sums holds the sums over the whole sequence)
-//   kFinalSum         comp = sum                        (plain column sums)
-enum { kFinalMean = 0, kFinalComplement = 1, kFinalSum = 2 };
+//   kFinalMean  comp = sum / N_d   (the streamed rows were the dropped set)
+//   kFinalSum   comp = sum         (plain column sums)
+enum { kFinalMean = 0, kFinalSum = 2 };
 
 template <int D, int MODE, class ROWS>
 __global__ void mean_final_kernel(const razor_head_desc *__restrict__ desc, int n_heads,
                                   const int32_t *__restrict__ prefix,
-                                  const float *__restrict__ partial,
-                                  const float *__restrict__ col_sums, float *__restrict__ comp)
+                                  const float *__restrict__ partial, float *__restrict__ comp)
 {
     __shared__ double red[4][2 * D];
     const int head = blockIdx.x, t = threadIdx.x, grp = threadIdx.y;
@@ -189,8 +186,7 @@ __global__ void mean_final_kernel(const razor_head_desc *__restrict__ desc, int 
         float out;
         if (MODE == kFinalSum) out = (float)sum;
         else if (e.n_dropped <= 0) out = 0.f;
-        else if (MODE == kFinalMean) out = (float)(sum / (double)e.n_dropped);
-        else out = (float)(((double)col_sums[(size_t)head * 2 * D + t] - sum) / (double)e.n_dropped);
+        else out = (float)(sum / (double)e.n_dropped);
         comp[(size_t)head * 2 * D + t] = out;
     }
 }
@@ -209,52 +205,137 @@ __device__ __forceinline__ int64_t source_row(int t, const razor_head_desc &e, i
 // block are written as zeros.  Workgroups are dispatched in (x, head) order, so at any moment
 // the chip reads and writes one moving window of each plane: measured 15 % faster for this
 // read + write traffic than giving every wave a private contiguous range.
-template <int RB>   // bytes per row
+//
+// SUMS (razor_compress given column sums): a head that dropped rows also needs the column sums
+// of its kept rows, and this kernel has them in registers anyway.  Each wave adds up its block,
+// the workgroup adds its four waves in order through LDS and stores one partial sum; the
+// workgroups of head i own the partial sums group_prefix[i] .. group_prefix[i + 1] - 1.
+template <int RB, int DTYPE, bool SUMS>   // RB: bytes per row
 __global__ __launch_bounds__(256) void compact_kernel(
     const char *__restrict__ K, const char *__restrict__ V, int64_t stride_b_bytes,
     int64_t stride_h_bytes, int64_t stride_n_bytes, const razor_head_desc *__restrict__ desc,
-    int n_kv_heads, int n_sink, char *__restrict__ arena)
+    int n_kv_heads, int n_sink, char *__restrict__ arena, const int32_t *__restrict__ group_prefix,
+    float *__restrict__ group_sums)
 {
     constexpr int LPR = RB / 16;       // 16-byte pieces per row
     constexpr int RPI = 64 / LPR;      // rows one wave-wide load covers
     constexpr int NI = kBlockRows / RPI;
+    constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
+    constexpr int NE = 16 / ES, D = RB / ES;
     __shared__ uint4 stage[4][kBlockRows * LPR];
+    __shared__ float wave_sums[SUMS ? 4 : 1][SUMS ? 2 * D : 1];
     const int head = blockIdx.y;
     const razor_head_desc e = desc[head];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int blk = blockIdx.x * 4 + wave;
-    if (blk >= (e.rows + kBlockRows - 1) / kBlockRows) return;   // wave-private work: no barrier
+    const int n_blocks = (e.rows + kBlockRows - 1) / kBlockRows;
+    const bool summing = SUMS && e.n_dropped > 0;
+    // the copy is wave-private work; only a summing workgroup meets at a barrier, so its idle
+    // waves stay until then
+    if (blockIdx.x * 4 >= n_blocks || (!summing && blk >= n_blocks)) return;
     const int prow = lane / LPR, piece = lane % LPR;
-    const int b = head / n_kv_heads, h = head % n_kv_heads;
-    const int64_t src_base = b * stride_b_bytes + h * stride_h_bytes + piece * 16;
-    char *kplane = arena + e.row_off * 2 * RB;
-    char *vplane = kplane + (int64_t)e.cap * RB;
+    float ak[NE], av[NE];
+#pragma unroll
+    for (int c = 0; c < NE; ++c) ak[c] = av[c] = 0.f;
 
-    uint4 kv[NI], vv[NI];
+    if (blk < n_blocks) {
+        const int b = head / n_kv_heads, h = head % n_kv_heads;
+        const int64_t src_base = b * stride_b_bytes + h * stride_h_bytes + piece * 16;
+        char *kplane = arena + e.row_off * 2 * RB;
+        char *vplane = kplane + (int64_t)e.cap * RB;
+
+        uint4 kv[NI], vv[NI];
 #pragma unroll
-    for (int r = 0; r < NI; ++r) {
-        const int t = blk * kBlockRows + r * RPI + prow;   // cache row
-        const bool valid = t < e.rows;
-        const int64_t off = src_base + source_row(valid ? t : e.rows - 1, e, n_sink) * stride_n_bytes;
-        kv[r] = stream_load16(K + off);
-        vv[r] = stream_load16(V + off);
-        if (!valid) kv[r] = vv[r] = make_uint4(0, 0, 0, 0);
+        for (int r = 0; r < NI; ++r) {
+            const int t = blk * kBlockRows + r * RPI + prow;   // cache row
+            const bool valid = t < e.rows;
+            const int64_t off = src_base + source_row(valid ? t : e.rows - 1, e, n_sink) * stride_n_bytes;
+            kv[r] = stream_load16(K + off);
+            vv[r] = stream_load16(V + off);
+            if (!valid) kv[r] = vv[r] = make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < NI; ++r) {
+            const int row = r * RPI + prow;
+            stream_store16(vplane + (int64_t)(blk * kBlockRows + row) * RB + piece * 16, vv[r]);
+            stage[wave][row * LPR + (piece ^ (row % LPR))] = kv[r];   // xor: conflict-free column reads
+            if (summing) {
+                accumulate_piece<DTYPE>(kv[r], ak);
+                accumulate_piece<DTYPE>(vv[r], av);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        char *kblock = kplane + (int64_t)blk * kBlockRows * RB;
+#pragma unroll
+        for (int s = 0; s < NI; ++s) {
+            const int pos = s * 64 + lane;                // 16-byte slot inside the block
+            const int c = pos / 16, r = pos % 16;         // piece-major: slot = c * 16 + r
+            stream_store16(kblock + (int64_t)pos * 16, stage[wave][r * LPR + (c ^ (r % LPR))]);
+        }
     }
+    if constexpr (SUMS) {
+        if (!summing) return;                             // uniform over the workgroup
 #pragma unroll
-    for (int r = 0; r < NI; ++r) {
-        const int row = r * RPI + prow;
-        stream_store16(vplane + (int64_t)(blk * kBlockRows + row) * RB + piece * 16, vv[r]);
-        stage[wave][row * LPR + (piece ^ (row % LPR))] = kv[r];   // xor: conflict-free column reads
+        for (int c = 0; c < NE; ++c) {
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) {
+                ak[c] += __shfl_xor(ak[c], o);
+                av[c] += __shfl_xor(av[c], o);
+            }
+        }
+        if (prow == 0) {
+#pragma unroll
+            for (int c = 0; c < NE; ++c) {
+                wave_sums[wave][piece * NE + c] = ak[c];
+                wave_sums[wave][D + piece * NE + c] = av[c];
+            }
+        }
+        __syncthreads();
+        float *dst = group_sums + (size_t)(group_prefix[head] + blockIdx.x) * 2 * D;
+        for (int t = threadIdx.x; t < 2 * D; t += 256)
+            dst[t] = ((wave_sums[0][t] + wave_sums[1][t]) + wave_sums[2][t]) + wave_sums[3][t];
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    char *kblock = kplane + (int64_t)blk * kBlockRows * RB;
-#pragma unroll
-    for (int s = 0; s < NI; ++s) {
-        const int pos = s * 64 + lane;                // 16-byte slot inside the block
-        const int c = pos / 16, r = pos % 16;         // piece-major: slot = c * 16 + r
-        stream_store16(kblock + (int64_t)pos * 16, stage[wave][r * LPR + (c ^ (r % LPR))]);
+}
+
+// Workgroups of the compaction kernel that hold kept rows of a head that dropped something.
+struct KeptGroupsOfCompressedHeads {
+    __device__ __forceinline__ int operator()(const razor_head_desc *__restrict__ desc, int idx) const
+    {
+        const int4 f = *reinterpret_cast<const int4 *>(reinterpret_cast<const char *>(desc + idx) + 16);
+        const int blocks = f.z > 0 ? (f.x + kBlockRows - 1) / kBlockRows : 0;   // {rows, cap, n_dropped, flags}
+        return (blocks + kGroupBlocks - 1) / kGroupBlocks;
+    }
+};
+
+__global__ __launch_bounds__(64) void group_prefix_kernel(const razor_head_desc *__restrict__ desc, int n_heads,
+                                                          int32_t *__restrict__ prefix)
+{
+    write_prefix(KeptGroupsOfCompressedHeads{}, desc, n_heads, (int)threadIdx.x, 0, prefix);
+}
+
+// Eq.(4) by complement: comp = (col_sums - sum over the head's kept rows) / N_d, the kept rows
+// given as the partial sums of the compaction kernel (four interleaved chains, each in index
+// order, then the chains in order, in double).  blockDim = (2 * D, 4).
+template <int D>
+__global__ void complement_final_kernel(const razor_head_desc *__restrict__ desc,
+                                        const int32_t *__restrict__ group_prefix,
+                                        const float *__restrict__ group_sums,
+                                        const float *__restrict__ col_sums, float *__restrict__ comp)
+{
+    __shared__ double red[4][2 * D];
+    const int head = blockIdx.x, t = threadIdx.x, grp = threadIdx.y;
+    const razor_head_desc e = desc[head];
+    double s = 0.0;
+    for (int k = group_prefix[head] + grp; k < group_prefix[head + 1]; k += 4)
+        s += (double)group_sums[(size_t)k * 2 * D + t];
+    red[grp][t] = s;
+    __syncthreads();
+    if (grp == 0) {
+        const double kept = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+        comp[(size_t)head * 2 * D + t] =
+            e.n_dropped > 0 ? (float)(((double)col_sums[(size_t)head * 2 * D + t] - kept) / (double)e.n_dropped) : 0.f;
     }
 }
 
@@ -277,7 +358,7 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
                     int64_t stride_h, int64_t stride_n, const std::vector<razor_head_desc> &desc,
                     int max_dropped, char *arena, float *comp, razor_head_desc *desc_dev,
                     int32_t *kept_idx_dev, const float *col_sums, int32_t *prefix, float *partial,
-                    int workers, hipStream_t stream)
+                    float *group_sums, int workers, hipStream_t stream)
 {
     constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
     const int n_heads = (int)desc.size();
@@ -298,24 +379,26 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
                            stride_b, stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads, p.n_sink,
                            workers, prefix, partial);
         hipLaunchKernelGGL((mean_final_kernel<D, kFinalMean, DroppedRows>), dim3(n_heads), dim3(2 * D, 4), 0,
-                           stream, desc_dev, n_heads, prefix, partial, col_sums, comp);
-    } else if (max_dropped > 0) {
-        // the caller already holds the column sums over the whole sequence (a prefill epilogue can
-        // accumulate them for free): stream only the few kept rows and take the complement
-        hipLaunchKernelGGL((mean_stream_kernel<DTYPE, D, KeptRowsOfCompressedHeads>), grid, dim3(256), 0,
-                           stream, K, V, stride_b, stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads,
-                           p.n_sink, workers, prefix, partial);
-        hipLaunchKernelGGL((mean_final_kernel<D, kFinalComplement, KeptRowsOfCompressedHeads>), dim3(n_heads),
-                           dim3(2 * D, 4), 0, stream, desc_dev, n_heads, prefix, partial, col_sums, comp);
-    } else {
+                           stream, desc_dev, n_heads, prefix, partial, comp);
+    } else if (max_dropped == 0) {
         hipLaunchKernelGGL((mean_final_kernel<D, kFinalMean, DroppedRows>), dim3(n_heads), dim3(2 * D, 4), 0,
-                           stream, desc_dev, n_heads, prefix, partial, col_sums, comp);
+                           stream, desc_dev, n_heads, prefix, partial, comp);
     }
-    if (max_rows > 0) {
-        const int groups = ((max_rows + kBlockRows - 1) / kBlockRows + 3) / 4;
-        hipLaunchKernelGGL((compact_kernel<D * ES>), dim3(groups, n_heads), dim3(256), 0, stream, K, V,
-                           stride_b * ES, stride_h * ES, stride_n * ES, desc_dev, p.n_kv_heads,
-                           p.n_sink, arena);
+    const int groups = ((max_rows + kBlockRows - 1) / kBlockRows + kGroupBlocks - 1) / kGroupBlocks;
+    if (max_dropped > 0 && col_sums) {
+        // the caller already holds the column sums over the whole sequence (a prefill epilogue can
+        // accumulate them for free): the dropped rows are not read at all; the compaction kernel
+        // adds up the kept rows it moves anyway and Eq.(4) is taken as the complement
+        hipLaunchKernelGGL(group_prefix_kernel, dim3(1), dim3(64), 0, stream, desc_dev, n_heads, prefix);
+        hipLaunchKernelGGL((compact_kernel<D * ES, DTYPE, true>), dim3(groups, n_heads), dim3(256), 0, stream, K, V,
+                           stride_b * ES, stride_h * ES, stride_n * ES, desc_dev, p.n_kv_heads, p.n_sink, arena,
+                           prefix, group_sums);
+        hipLaunchKernelGGL((complement_final_kernel<D>), dim3(n_heads), dim3(2 * D, 4), 0, stream, desc_dev,
+                           prefix, group_sums, col_sums, comp);
+    } else if (max_rows > 0) {
+        hipLaunchKernelGGL((compact_kernel<D * ES, DTYPE, false>), dim3(groups, n_heads), dim3(256), 0, stream, K, V,
+                           stride_b * ES, stride_h * ES, stride_n * ES, desc_dev, p.n_kv_heads, p.n_sink, arena,
+                           nullptr, nullptr);
     }
     if (kept_idx_dev && max_rows > 0) {
         const int gx = std::min((max_rows + 255) / 256, 64);
@@ -345,7 +428,7 @@ int launch_column_sums(const razor_params &p, const char *K, const char *V, int6
                        stream, K, V, stride_b, stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads,
                        p.n_sink, workers, prefix, partial);
     hipLaunchKernelGGL((mean_final_kernel<D, kFinalSum, AllRows>), dim3(n_heads), dim3(2 * D, 4), 0, stream,
-                       desc_dev, n_heads, prefix, partial, nullptr, sums);
+                       desc_dev, n_heads, prefix, partial, sums);
     RAZOR_HIP_CHECK(hipGetLastError());
     return RAZOR_OK;
 }
@@ -422,11 +505,13 @@ extern "C" int razor_compress(const razor_params *p, const void *K, const void *
     std::vector<razor_head_desc> desc;
     razor_sizes sizes;
     int max_dropped = 0;
-    int rc = build_plan(*p, seq_lens_host, retrieval_mask_host, desc, sizes, max_dropped);
+    size_t group_bytes = 0;
+    int rc = build_plan(*p, seq_lens_host, retrieval_mask_host, desc, sizes, max_dropped, &group_bytes);
     if (rc != RAZOR_OK) return rc;
     if (sizes.arena_bytes > 0 && !arena) return RAZOR_EINVAL;
     const CompressWorkspace ws = compress_workspace(*p);
-    if (!workspace || workspace_bytes < ws.bytes) return RAZOR_ECAPACITY;
+    if (!workspace || workspace_bytes < ws.bytes + (col_sums ? group_bytes : 0)) return RAZOR_ECAPACITY;
+    float *group_sums = reinterpret_cast<float *>(static_cast<char *>(workspace) + ws.bytes);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const char *k = static_cast<const char *>(K), *v = static_cast<const char *>(V);
@@ -441,7 +526,7 @@ extern "C" int razor_compress(const razor_params *p, const void *K, const void *
     workers = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
 #define RAZOR_DISPATCH(DT, DD)                                                                    \
     return launch_compress<DT, DD>(*p, k, v, stride_b, stride_h, stride_n, desc, max_dropped, a,  \
-                                   comp, desc_dev, kept_idx_dev, col_sums, prefix, partial, workers, s)
+                                   comp, desc_dev, kept_idx_dev, col_sums, prefix, partial, group_sums, workers, s)
     if (p->dtype == RAZOR_BF16 && p->head_dim == 128) RAZOR_DISPATCH(RAZOR_BF16, 128);
     if (p->dtype == RAZOR_BF16 && p->head_dim == 64) RAZOR_DISPATCH(RAZOR_BF16, 64);
     if (p->dtype == RAZOR_F32 && p->head_dim == 128) RAZOR_DISPATCH(RAZOR_F32, 128);

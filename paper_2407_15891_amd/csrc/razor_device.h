@@ -77,13 +77,6 @@ struct DroppedRows {      // the set D of Eq.(4)
     static __device__ __forceinline__ int n(int rows, int n_dropped) { return n_dropped; }
     static __device__ __forceinline__ int64_t row(int t, int rows, int n_dropped, int n_sink) { return (int64_t)n_sink + t; }
 };
-struct KeptRowsOfCompressedHeads {   // sinks + window of the heads that dropped rows
-    static __device__ __forceinline__ int n(int rows, int n_dropped) { return n_dropped > 0 ? rows : 0; }
-    static __device__ __forceinline__ int64_t row(int t, int rows, int n_dropped, int n_sink)
-    {
-        return t < n_sink ? (int64_t)t : (int64_t)t + n_dropped;
-    }
-};
 struct AllRows {          // every valid row of the sequence
     static __device__ __forceinline__ int n(int rows, int n_dropped) { return rows + n_dropped; }
     static __device__ __forceinline__ int64_t row(int t, int rows, int n_dropped, int n_sink) { return t; }

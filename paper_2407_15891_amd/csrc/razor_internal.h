@@ -11,6 +11,10 @@
 namespace razor {
 
 constexpr int kBlockRows = RAZOR_BLOCK_ROWS;  // K rows per arena block
+// razor_compress given column sums: the compaction kernel also adds up the kept rows of the heads
+// that dropped something, one partial sum per workgroup (kGroupBlocks 16-row blocks); they live
+// behind the rest of the compress workspace.
+constexpr int kGroupBlocks = 4;
 constexpr int kMinBlocksPerWorker = 2;        // never split a decode finer than this
 
 inline int elem_size(int dtype) { return dtype == RAZOR_F32 ? 4 : 2; }
@@ -44,7 +48,8 @@ int check_params(const razor_params *p);
 
 // Fills desc (size batch * n_kv_heads); returns RAZOR_OK / RAZOR_EINVAL.
 int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *mask,
-               std::vector<razor_head_desc> &desc, razor_sizes &sizes, int &max_dropped);
+               std::vector<razor_head_desc> &desc, razor_sizes &sizes, int &max_dropped,
+               size_t *group_sum_bytes = nullptr);
 
 // Remembers `what` + the HIP error text for razor_strerror; returns RAZOR_EHIP.
 int hip_failure(const char *what, int hip_error);
