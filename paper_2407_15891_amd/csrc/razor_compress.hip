@@ -328,8 +328,18 @@ __global__ void complement_final_kernel(const razor_head_desc *__restrict__ desc
     const int head = blockIdx.x, t = threadIdx.x, grp = threadIdx.y;
     const razor_head_desc e = desc[head];
     double s = 0.0;
-    for (int k = group_prefix[head] + grp; k < group_prefix[head + 1]; k += 4)
-        s += (double)group_sums[(size_t)k * 2 * D + t];
+    // chain grp takes the partial sums first + grp, first + grp + 4, ...; eight loads are issued
+    // together, the additions keep their order
+    const int first = group_prefix[head], last = group_prefix[head + 1];
+    int k = first + grp;
+    for (; k + 28 < last; k += 32) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = group_sums[(size_t)(k + 4 * u) * 2 * D + t];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (double)v[u];
+    }
+    for (; k < last; k += 4) s += (double)group_sums[(size_t)k * 2 * D + t];
     red[grp][t] = s;
     __syncthreads();
     if (grp == 0) {
