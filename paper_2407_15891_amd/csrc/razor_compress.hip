@@ -4,6 +4,9 @@
 //   copy   kept rows (sinks + window, or everything) -> arena; K re-tiled through LDS
 //   index  kept positions as int32 (optional)
 // All of it is HBM streaming: every source row is read once, kept rows written once.
+// Given the column sums over the whole sequence (razor_column_sums, or a prefill epilogue) the
+// dropped rows are not read: the copy adds up the kept rows it moves and the mean is taken
+// from the difference.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
