@@ -86,7 +86,8 @@ typedef struct razor_params {
     int32_t out_dtype;   /* razor_dtype of O */
     float scale;         /* multiplies every logit, the compensation logit included; 1.0f is
                             Eq.(5) as printed, 1/sqrt(head_dim) what the evaluated models use */
-    int32_t n_workers;   /* wavefronts to split a decode over; 0 = pick from the device */
+    int32_t n_workers;   /* wavefronts to split a pass over; 0 = pick from the device: one per SIMD
+                            (four per compute unit), two for decode over 128-byte rows */
     int32_t sliding;     /* 0: compress once, decode appends and never evicts.
                             1: Algorithm 1 re-applied after every generated token: once a
                             non-retrieval head holds n_sink + window rows, an append overwrites its

@@ -726,6 +726,11 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
     if (workers == 0) {
         int rc = auto_workers(&workers);
         if (rc != RAZOR_OK) return rc;
+        // A 16-row block of 128-byte rows (bf16, head_dim 64) is only 4 KB, and the chain of
+        // dependent steps per block costs a wave as long as for 8 KB: a second wave per SIMD
+        // hides it (859 MB cache: 4.4 TB/s with one wave per SIMD, 6.4 with two; every other
+        // row size is at its best with one).
+        if (p->dtype == RAZOR_BF16 && p->head_dim == 64) workers *= 2;
     }
     workers = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
 
