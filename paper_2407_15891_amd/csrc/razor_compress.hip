@@ -484,6 +484,9 @@ extern "C" int razor_column_sums(const razor_params *p, const void *K, const voi
     if (workers == 0) {
         rc = auto_workers(&workers);
         if (rc != RAZOR_OK) return rc;
+        // 128-byte rows: a wave has half the bytes in flight, two waves per SIMD make up for it
+        // (column sums of a 2.1 GB cache: 415 us with one wave per SIMD)
+        if (p->head_dim * elem_size(p->dtype) == 128) workers *= 2;
     }
     workers = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
     char *wsb = static_cast<char *>(workspace);
@@ -535,6 +538,9 @@ extern "C" int razor_compress(const razor_params *p, const void *K, const void *
     if (workers == 0) {
         rc = auto_workers(&workers);
         if (rc != RAZOR_OK) return rc;
+        // 128-byte rows: a wave has half the bytes in flight, two waves per SIMD make up for it
+        // (column sums of a 2.1 GB cache: 415 us with one wave per SIMD)
+        if (p->head_dim * elem_size(p->dtype) == 128) workers *= 2;
     }
     workers = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
 #define RAZOR_DISPATCH(DT, DD)                                                                    \
