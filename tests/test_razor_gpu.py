@@ -172,6 +172,10 @@ def test_compress_strided_input_and_fp32_dim128():
     (3, 3001, 500, 3, 24),
     (4, 8000, 300, 4, 0),      # GQA g = 8, ragged lengths
     (4, 2500, 77, 6, 40),
+    (3, 3001, 500, 3, 7),      # worker counts that are no multiple of a workgroup's four waves
+    (2, 1500, 200, 2, 1023),
+    (1, 777, 90, 2, 1),        # a single wave does everything
+    (4, 2500, 77, 6, 8192),    # far more waves than blocks
 ])
 def test_decode_parity(cfg, context, window, batch, workers):
     say(f"decode parity cfg={cfg} context={context} window={window} batch={batch} workers={workers}")
