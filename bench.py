@@ -214,7 +214,8 @@ def run_head_scores(args, ev):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kernel_ms = ev.elapsed_ms(a, b) / steps
-    flops = Hq * (N * (N + 1) // 2) * 2 * d         # causal half of Q K^T, multiply + add
+    logits = Hq * (N * (N + 1) // 2)                # causal half of Q K^T
+    flops = logits * 2 * d                          # multiply + add
     tflops = flops / (kernel_ms * 1e-3) / 1e12
     cpu = None
     if not args.no_cpu_baseline:
@@ -234,7 +235,13 @@ def run_head_scores(args, ev):
         "config": {"workload": f"2500 random tokens x 4, {layers} layers of 32/8 heads x 128, one call"},
         "heads_per_s": Hq / (kernel_ms * 1e-3),
         "roofline": {"bound": "mfma", "kernel": "head_scores_kernel<128>", "achieved": tflops, "peak": 2500.0,
-                     "unit": "TFLOP/s", "frac": tflops / 2500.0, "kernel_ms": kernel_ms, "traffic": None},
+                     "unit": "TFLOP/s", "frac": tflops / 2500.0, "kernel_ms": kernel_ms, "traffic": None,
+                     # what actually limits the kernel: vector issue slots.  Per logit one fma, one exp2
+                     # (two slots) and one add; 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz slots per second
+                     # (packed fp32 is not used in this build)
+                     "vector_issue": {"slots_per_logit": 4, "achieved_Tslots": logits * 4 / (kernel_ms * 1e-3) / 1e12,
+                                      "peak_Tslots": 256 * 4 * 16 * 2.4e9 / 1e12,
+                                      "frac": logits * 4 / (kernel_ms * 1e-3) / (256 * 4 * 16 * 2.4e9)}},
         "cpu_baseline": cpu,
     }))
 
