@@ -403,7 +403,7 @@ def main():
             for r in range(reps + 2):
                 addr = probe_buf.data_ptr() + (r % slots) * nbytes
                 ev.record(a0, stream)
-                rc = razor.razor_probe_read_stream(addr, nbytes, args.workers, sink, stream)
+                rc = razor.razor_probe_read_stream(addr, nbytes, args.workers, 0, 2, 1, sink, stream)
                 assert rc == 0, razor.razor_strerror(rc)
                 ev.record(b0, stream)
                 ms = ev.elapsed_ms(a0, b0)

@@ -20,7 +20,8 @@
  *   - The library owns no memory and keeps no state between calls.  The caller
  *     allocates every buffer with the sizes razor_plan reports.  Device calls
  *     only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
- *     default stream); they never allocate, never synchronise.
+ *     default stream); they never allocate, never synchronise.  One exception,
+ *     opt-in: the measurement hooks of razor_bench.h keep per-thread state.
  *   - All functions return RAZOR_OK (0) or a negative razor_status.  Arguments
  *     are validated on the host before anything is enqueued; a failing call
  *     enqueues nothing.
@@ -40,8 +41,12 @@
  *           so that one wavefront-wide 128-bit load yields a matrix-core
  *           operand without a transpose.
  *   comp    float32 [batch, n_kv_heads, 2, head_dim]: khat then vhat of Eq.(4)
- *           (zeros for heads that dropped nothing).
- *   desc    razor_head_desc[batch * n_kv_heads], index b * n_kv_heads + h.
+ *           (zeros for heads that dropped nothing).  With params.sliding = 1 a second array
+ *           of the same shape follows: the low-order parts of the running means, which
+ *           keep their update exact over generations of any length (comp_bytes of
+ *           razor_sizes covers both).
+ *   desc    razor_head_desc[batch * n_kv_heads], index b * n_kv_heads + h; the device copy
+ *           must be 16-byte aligned like every other device buffer handed to the library.
  */
 #ifndef RAZOR_H
 #define RAZOR_H
@@ -60,7 +65,7 @@ typedef enum razor_dtype { RAZOR_F32 = 0, RAZOR_BF16 = 1 } razor_dtype;
 typedef enum razor_status {
     RAZOR_OK = 0,
     RAZOR_EINVAL = -1,     /* null pointer, unsupported dtype / head_dim / group size, bad length or stride */
-    RAZOR_ECAPACITY = -2,  /* workspace smaller than razor_plan asked for */
+    RAZOR_ECAPACITY = -2,  /* a workspace is smaller than asked for (razor_strerror names it) */
     RAZOR_EHIP = -3        /* a HIP runtime call failed (razor_strerror gives its text) */
 } razor_status;
 
@@ -72,9 +77,10 @@ typedef enum razor_status {
 #define RAZOR_BLOCK_ROWS 16    /* K rows per arena block                                       */
 #define RAZOR_MAX_GROUP 16     /* largest n_q_heads / n_kv_heads                               */
 #define RAZOR_MAX_WORKERS 8192 /* upper bound on wavefronts a decode launch splits the cache over */
+#define RAZOR_MAX_HEADS 65535  /* largest batch * n_kv_heads of one call                          */
 
 typedef struct razor_params {
-    int32_t batch;       /* B >= 1 */
+    int32_t batch;       /* B >= 1; batch * n_kv_heads <= RAZOR_MAX_HEADS */
     int32_t n_q_heads;   /* H_q, multiple of n_kv_heads, group size <= RAZOR_MAX_GROUP */
     int32_t n_kv_heads;  /* H_kv */
     int32_t head_dim;    /* 64 or 128 */
@@ -118,6 +124,9 @@ typedef struct razor_head_desc {
     int32_t evicted;   /* sliding mode: rows overwritten so far; the next one is row
                           n_sink + evicted % window                                        */
     int32_t window;    /* buffer length of this head (p->window or head_window_host[h])    */
+    int32_t reserved[2]; /* zero; pads an entry to 48 bytes so that {rows, cap, n_dropped,
+                          flags} of every entry of a 16-byte aligned table can be fetched
+                          with one aligned 128-bit load                                    */
 } razor_head_desc;
 
 typedef struct razor_sizes {
@@ -233,29 +242,9 @@ RAZOR_API int razor_select_heads(const float *echo_host, const float *induction_
                        int n_heads, int group, double frac_induction, double frac_echo,
                        uint8_t *mask_host);
 
-/*
- * Measurement hook.  After this call, every razor_decode_attn issued by the calling
- * thread records ev_start (a hipEvent_t) on its stream right before the kernel that
- * streams the cache and ev_stop right after it, so a benchmark can time that kernel
- * alone.  Pass NULL, NULL to switch the hook off (the default).  The events stay owned
- * by the caller.  Always returns RAZOR_OK.
- */
-RAZOR_API int razor_profile_events(void *ev_start, void *ev_stop);
-
-/*
- * Measurement hook: the read-stream ceiling.  Reads the first bytes / 4096 * 4096 bytes at buf
- * (device, 16-byte aligned, at least 4096 bytes) exactly once with the access pattern of the
- * streaming kernels -- one contiguous range per wavefront, 128-bit non-temporal loads -- and
- * does no other work, so the duration of this launch is what the device gives a kernel that only
- * reads.  n_workers: 0 = four wavefronts per compute unit, as in the parameter block.  sink: device,
- * at least 4 * RAZOR_MAX_WORKERS bytes, may be written (it keeps the loads alive).  Enqueued on
- * `stream`; time it with events.
- */
-RAZOR_API int razor_probe_read_stream(const void *buf, size_t bytes, int n_workers, void *sink,
-                            void *stream);
-
 /* Text for a razor_status; for RAZOR_EHIP the text of the last HIP error seen by the
- * calling thread.  The pointer stays valid until the thread's next failing call. */
+ * calling thread, for RAZOR_ECAPACITY the buffer its last such failure found too small.
+ * The pointer stays valid until the thread's next failing call. */
 RAZOR_API const char *razor_strerror(int status);
 
 #ifdef __cplusplus

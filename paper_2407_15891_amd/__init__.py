@@ -1,8 +1,9 @@
 """Python binding of the razor C-ABI library (RazorAttention hot path on MI355X).
 
 The functions `razor_plan`, `razor_compress`, `razor_column_sums`, `razor_decode_attn`,
-`razor_head_scores`, `razor_head_scores_workspace`, `razor_select_heads`, `razor_profile_events`,
-`razor_probe_read_stream` and `razor_strerror` carry the names and the argument order of `include/razor.h`; they only marshal
+`razor_head_scores`, `razor_head_scores_workspace`, `razor_select_heads`
+and `razor_strerror` carry the names and the argument order of `include/razor.h`
+(`razor_profile_events`, `razor_probe_read_stream`, `razor_probe_copy`: `include/razor_bench.h`); they only marshal
 arguments (torch tensors -> device pointers, numpy arrays -> host pointers).  Every
 step of the path runs in the HIP kernels of `librazor.so`; there is no Python or CPU
 fallback: a missing library raises on first use.
@@ -28,9 +29,14 @@ RAZOR_BLOCK_ROWS = 16
 RAZOR_MAX_GROUP = 16
 RAZOR_MAX_WORKERS = 8192
 
+RAZOR_MAX_HEADS = 65535
+RAZOR_PROBE_CONTIGUOUS, RAZOR_PROBE_INTERLEAVED = 0, 1
+
+# include/razor.h, then the measurement hooks of include/razor_bench.h
 EXPORTS = ("razor_plan", "razor_compress", "razor_column_sums", "razor_decode_attn",
-           "razor_head_scores_workspace", "razor_head_scores", "razor_select_heads",
-           "razor_profile_events", "razor_probe_read_stream", "razor_strerror")
+           "razor_head_scores_workspace", "razor_head_scores",
+           "razor_select_heads", "razor_strerror",
+           "razor_profile_events", "razor_probe_read_stream", "razor_probe_copy")
 
 
 class RazorParams(ctypes.Structure):
@@ -48,7 +54,8 @@ class RazorHeadDesc(ctypes.Structure):
     _fields_ = [("row_off", ctypes.c_int64), ("kept_off", ctypes.c_int64),
                 ("rows", ctypes.c_int32), ("cap", ctypes.c_int32),
                 ("n_dropped", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("evicted", ctypes.c_int32), ("window", ctypes.c_int32)]
+                ("evicted", ctypes.c_int32), ("window", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
 
 
 class RazorSizes(ctypes.Structure):
@@ -59,8 +66,9 @@ class RazorSizes(ctypes.Structure):
 
 
 DESC_DTYPE = np.dtype([("row_off", "<i8"), ("kept_off", "<i8"), ("rows", "<i4"), ("cap", "<i4"),
-                       ("n_dropped", "<i4"), ("flags", "<u4"), ("evicted", "<i4"), ("window", "<i4")])
-assert DESC_DTYPE.itemsize == ctypes.sizeof(RazorHeadDesc) == 40
+                       ("n_dropped", "<i4"), ("flags", "<u4"), ("evicted", "<i4"), ("window", "<i4"),
+                       ("reserved", "<i4", (2,))])
+assert DESC_DTYPE.itemsize == ctypes.sizeof(RazorHeadDesc) == 48
 
 
 class RazorError(RuntimeError):
@@ -102,7 +110,9 @@ def load_library():
     L.razor_profile_events.restype = ctypes.c_int
     L.razor_profile_events.argtypes = [vp, vp]
     L.razor_probe_read_stream.restype = ctypes.c_int
-    L.razor_probe_read_stream.argtypes = [vp, sz, ctypes.c_int, vp, vp]
+    L.razor_probe_read_stream.argtypes = [vp, sz, ci, ci, ci, ci, vp, vp]
+    L.razor_probe_copy.restype = ctypes.c_int
+    L.razor_probe_copy.argtypes = [vp, vp, sz, ci, ci, ci, vp]
     L.razor_strerror.restype = ctypes.c_char_p
     L.razor_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -189,10 +199,20 @@ def razor_profile_events(ev_start, ev_stop) -> int:
     return load_library().razor_profile_events(ev_start, ev_stop)
 
 
-def razor_probe_read_stream(buf, nbytes: int, n_workers: int, sink, stream: int = 0) -> int:
+def razor_probe_read_stream(buf, nbytes: int, n_workers: int, pattern: int, depth: int, nontemporal: int,
+                            sink, stream: int = 0) -> int:
     """buf: device tensor, or a raw device address (int) inside one."""
     addr = buf if isinstance(buf, int) else _dev(buf)
-    return load_library().razor_probe_read_stream(addr, nbytes, n_workers, _dev(sink), stream or None)
+    return load_library().razor_probe_read_stream(addr, nbytes, n_workers, pattern, depth, nontemporal,
+                                                  _dev(sink), stream or None)
+
+
+def razor_probe_copy(dst, src, nbytes: int, n_workers: int, pattern: int, nontemporal: int,
+                     stream: int = 0) -> int:
+    """dst, src: device tensors, or raw device addresses (int)."""
+    d = dst if isinstance(dst, int) else _dev(dst)
+    s = src if isinstance(src, int) else _dev(src)
+    return load_library().razor_probe_copy(d, s, nbytes, n_workers, pattern, nontemporal, stream or None)
 
 
 def _check(status: int, where: str) -> None:
@@ -266,7 +286,7 @@ class RazorCache:
         self.device = torch.device(device)
         u8 = dict(dtype=torch.uint8, device=self.device)
         self.arena = torch.empty(max(int(self.sizes.arena_bytes), 16), **u8)
-        self.comp = torch.empty(batch * n_kv_heads * 2 * head_dim, dtype=torch.float32, device=self.device)
+        self.comp = torch.empty(int(self.sizes.comp_bytes) // 4, dtype=torch.float32, device=self.device)
         self.desc_dev = torch.empty(int(self.sizes.desc_bytes), **u8)
         self.workspace = torch.empty(int(self.sizes.workspace_bytes), **u8)
         self.kept_idx_dev = (torch.empty(max(int(self.sizes.total_rows), 1), dtype=torch.int32,
@@ -324,6 +344,13 @@ class RazorCache:
         _check(razor_decode_attn(p, Q, k_new, v_new, self.arena, self.comp, self.desc_dev, out,
                                  self.workspace, self.workspace.numel(), self._stream()), "razor_decode_attn")
         return out
+
+    def comp_tokens(self):
+        """khat, vhat of Eq.(4) as a [B, H_kv, 2, d] view of `comp` (in sliding mode the buffer also
+        holds the low-order parts of the running means behind them)."""
+        p = self.params
+        n = p.batch * p.n_kv_heads * 2 * p.head_dim
+        return self.comp[:n].view(p.batch, p.n_kv_heads, 2, p.head_dim)
 
     def desc(self) -> np.ndarray:
         """Device descriptor table copied to the host (synchronises)."""

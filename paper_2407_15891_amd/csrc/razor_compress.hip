@@ -170,7 +170,8 @@ enum { kFinalMean = 0, kFinalSum = 2 };
 template <int D, int MODE, class ROWS>
 __global__ void mean_final_kernel(const razor_head_desc *__restrict__ desc, int n_heads,
                                   const int32_t *__restrict__ prefix,
-                                  const float *__restrict__ partial, float *__restrict__ comp)
+                                  const float *__restrict__ partial, float *__restrict__ comp,
+                                  float *__restrict__ comp_lo)
 {
     __shared__ double red[4][2 * D];
     const int head = blockIdx.x, t = threadIdx.x, grp = threadIdx.y;
@@ -191,6 +192,7 @@ __global__ void mean_final_kernel(const razor_head_desc *__restrict__ desc, int 
         else if (e.n_dropped <= 0) out = 0.f;
         else out = (float)(sum / (double)e.n_dropped);
         comp[(size_t)head * 2 * D + t] = out;
+        if (comp_lo) comp_lo[(size_t)head * 2 * D + t] = 0.f;   // low-order parts of the sliding-mode means
     }
 }
 
@@ -306,8 +308,8 @@ __global__ __launch_bounds__(256) void compact_kernel(
 struct KeptGroupsOfCompressedHeads {
     __device__ __forceinline__ int operator()(const razor_head_desc *__restrict__ desc, int idx) const
     {
-        const int4 f = *reinterpret_cast<const int4 *>(reinterpret_cast<const char *>(desc + idx) + 16);
-        const int blocks = f.z > 0 ? (f.x + kBlockRows - 1) / kBlockRows : 0;   // {rows, cap, n_dropped, flags}
+        const int4 f = desc_counts(desc, idx);
+        const int blocks = f.z > 0 ? (f.x + kBlockRows - 1) / kBlockRows : 0;
         return (blocks + kGroupBlocks - 1) / kGroupBlocks;
     }
 };
@@ -325,7 +327,8 @@ template <int D>
 __global__ void complement_final_kernel(const razor_head_desc *__restrict__ desc,
                                         const int32_t *__restrict__ group_prefix,
                                         const float *__restrict__ group_sums,
-                                        const float *__restrict__ col_sums, float *__restrict__ comp)
+                                        const float *__restrict__ col_sums, float *__restrict__ comp,
+                                        float *__restrict__ comp_lo)
 {
     __shared__ double red[4][2 * D];
     const int head = blockIdx.x, t = threadIdx.x, grp = threadIdx.y;
@@ -349,6 +352,7 @@ __global__ void complement_final_kernel(const razor_head_desc *__restrict__ desc
         const double kept = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
         comp[(size_t)head * 2 * D + t] =
             e.n_dropped > 0 ? (float)(((double)col_sums[(size_t)head * 2 * D + t] - kept) / (double)e.n_dropped) : 0.f;
+        if (comp_lo) comp_lo[(size_t)head * 2 * D + t] = 0.f;
     }
 }
 
@@ -375,6 +379,7 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
 {
     constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
     const int n_heads = (int)desc.size();
+    float *comp_lo = p.sliding ? comp + (size_t)n_heads * 2 * D : nullptr;
     for (int first = 0; first < n_heads; first += kDescPerLaunch) {
         DescBatch batch;
         const int count = std::min(kDescPerLaunch, n_heads - first);
@@ -392,10 +397,10 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
                            stride_b, stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads, p.n_sink,
                            workers, prefix, partial);
         hipLaunchKernelGGL((mean_final_kernel<D, kFinalMean, DroppedRows>), dim3(n_heads), dim3(2 * D, 4), 0,
-                           stream, desc_dev, n_heads, prefix, partial, comp);
+                           stream, desc_dev, n_heads, prefix, partial, comp, comp_lo);
     } else if (max_dropped == 0) {
         hipLaunchKernelGGL((mean_final_kernel<D, kFinalMean, DroppedRows>), dim3(n_heads), dim3(2 * D, 4), 0,
-                           stream, desc_dev, n_heads, prefix, partial, comp);
+                           stream, desc_dev, n_heads, prefix, partial, comp, comp_lo);
     }
     const int groups = ((max_rows + kBlockRows - 1) / kBlockRows + kGroupBlocks - 1) / kGroupBlocks;
     if (max_dropped > 0 && col_sums) {
@@ -403,11 +408,12 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
         // accumulate them for free): the dropped rows are not read at all; the compaction kernel
         // adds up the kept rows it moves anyway and Eq.(4) is taken as the complement
         hipLaunchKernelGGL(group_prefix_kernel, dim3(1), dim3(64), 0, stream, desc_dev, n_heads, prefix);
-        hipLaunchKernelGGL((compact_kernel<D * ES, DTYPE, true>), dim3(groups, n_heads), dim3(256), 0, stream, K, V,
-                           stride_b * ES, stride_h * ES, stride_n * ES, desc_dev, p.n_kv_heads, p.n_sink, arena,
-                           prefix, group_sums);
+        if (max_rows > 0)   // no head keeps a row (no sinks, no window): comp = col_sums / N_d below
+            hipLaunchKernelGGL((compact_kernel<D * ES, DTYPE, true>), dim3(groups, n_heads), dim3(256), 0, stream, K, V,
+                               stride_b * ES, stride_h * ES, stride_n * ES, desc_dev, p.n_kv_heads, p.n_sink, arena,
+                               prefix, group_sums);
         hipLaunchKernelGGL((complement_final_kernel<D>), dim3(n_heads), dim3(2 * D, 4), 0, stream, desc_dev,
-                           prefix, group_sums, col_sums, comp);
+                           prefix, group_sums, col_sums, comp, comp_lo);
     } else if (max_rows > 0) {
         hipLaunchKernelGGL((compact_kernel<D * ES, DTYPE, false>), dim3(groups, n_heads), dim3(256), 0, stream, K, V,
                            stride_b * ES, stride_h * ES, stride_n * ES, desc_dev, p.n_kv_heads, p.n_sink, arena,
@@ -441,7 +447,7 @@ int launch_column_sums(const razor_params &p, const char *K, const char *V, int6
                        stream, K, V, stride_b, stride_h, stride_n, desc_dev, n_heads, p.n_kv_heads,
                        p.n_sink, workers, prefix, partial);
     hipLaunchKernelGGL((mean_final_kernel<D, kFinalSum, AllRows>), dim3(n_heads), dim3(2 * D, 4), 0, stream,
-                       desc_dev, n_heads, prefix, partial, sums);
+                       desc_dev, n_heads, prefix, partial, sums, nullptr);
     RAZOR_HIP_CHECK(hipGetLastError());
     return RAZOR_OK;
 }
@@ -479,7 +485,8 @@ extern "C" int razor_column_sums(const razor_params *p, const void *K, const voi
     int rc = build_plan(*p, seq_lens_host, all.data(), desc, sizes, max_dropped);
     if (rc != RAZOR_OK) return rc;
     const CompressWorkspace ws = compress_workspace(*p);
-    if (!workspace || workspace_bytes < ws.bytes) return RAZOR_ECAPACITY;
+    if (!workspace || workspace_bytes < ws.bytes)
+        return capacity_failure("razor_column_sums: workspace smaller than razor_plan reported");
     int workers = p->n_workers;
     if (workers == 0) {
         rc = auto_workers(&workers);
@@ -516,7 +523,9 @@ extern "C" int razor_compress(const razor_params *p, const void *K, const void *
     using namespace razor;
     if (check_source(p, K, V, stride_b, stride_h, stride_n) != RAZOR_OK) return RAZOR_EINVAL;
     if (!seq_lens_host || !retrieval_mask_host || !comp || !desc_dev) return RAZOR_EINVAL;
-    if (((uintptr_t)arena | (uintptr_t)comp | (uintptr_t)col_sums) & 15) return RAZOR_EINVAL;
+    if (((uintptr_t)arena | (uintptr_t)comp | (uintptr_t)col_sums | (uintptr_t)desc_dev | (uintptr_t)workspace) & 15)
+        return RAZOR_EINVAL;
+    if ((uintptr_t)kept_idx_dev & 3) return RAZOR_EINVAL;
 
     std::vector<razor_head_desc> desc;
     razor_sizes sizes;
@@ -526,7 +535,8 @@ extern "C" int razor_compress(const razor_params *p, const void *K, const void *
     if (rc != RAZOR_OK) return rc;
     if (sizes.arena_bytes > 0 && !arena) return RAZOR_EINVAL;
     const CompressWorkspace ws = compress_workspace(*p);
-    if (!workspace || workspace_bytes < ws.bytes + (col_sums ? group_bytes : 0)) return RAZOR_ECAPACITY;
+    if (!workspace || workspace_bytes < ws.bytes + (col_sums ? group_bytes : 0))
+        return capacity_failure("razor_compress: workspace smaller than razor_plan reported");
     float *group_sums = reinterpret_cast<float *>(static_cast<char *>(workspace) + ws.bytes);
 
     hipStream_t s = static_cast<hipStream_t>(stream);

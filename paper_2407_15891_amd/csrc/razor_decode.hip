@@ -24,6 +24,7 @@
 #include <cmath>
 #include <type_traits>
 
+#include "razor_bench.h"
 #include "razor_device.h"
 #include "razor_internal.h"
 
@@ -38,13 +39,14 @@ constexpr float kNegInf = -__builtin_huge_valf();
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Debug builds (-DRAZOR_TIMELINE) stamp the 100 MHz wall clock at a few points of every
-// streaming wave and drop the stamps behind the last partial slot; off in the product.
+// streaming wave and drop the stamps into the unused upper half of the partial-output slots
+// (such builds run at most RAZOR_MAX_WORKERS / 2 waves); off in the product.
 #ifdef RAZOR_TIMELINE
 #define RAZOR_STAMP(k) long long stamp_##k = wall_clock64()
 #define RAZOR_STAMP_SEG() ++stamp_segments
 #define RAZOR_STAMP_FLUSH()                                                                        \
     if (lane == 0) {                                                                               \
-        long long *dst = reinterpret_cast<long long *>(part_acc + (size_t)7000 * g * D) + (size_t)w * 4;        \
+        long long *dst = reinterpret_cast<long long *>(part_acc + timeline_floats(n_heads, g, D)) + (size_t)w * 4; \
         dst[0] = stamp_0; dst[1] = stamp_1; dst[2] = stamp_2; dst[3] = stamp_segments;             \
     }
 #else
@@ -81,11 +83,17 @@ __device__ __forceinline__ void append_row(const razor_head_desc &e, int head, c
 // dropped set enlarged by that row -- and is then overwritten by the new token.  Lanes
 // 0..LPR-1 handle the K pieces, lanes 32..32+LPR-1 the V pieces.  Called by the one wave whose
 // range holds the row's block; comp is not read by anyone else before the combine kernel.
+//
+// The mean is carried as an unevaluated fp32 pair hi + lo (hi in comp, lo in comp_lo): the
+// increment is added with an error-free transformation, so what each addition rounds away
+// stays in lo instead of piling up.  A plain fp32 update drifts like the square root of the
+// number of steps (about 40 ulp of the mean after a million evictions); the pair stays within
+// an ulp of the exact mean of Eq.(4) for generations of any length.
 template <int RB, int DTYPE>
 __device__ __forceinline__ void evict_row(const razor_head_desc &e, int head, int slot, char *kplane,
                                           char *vplane, const char *__restrict__ k_new,
                                           const char *__restrict__ v_new, float *__restrict__ comp,
-                                          int lane)
+                                          float *__restrict__ comp_lo, int lane)
 {
     constexpr int LPR = RB / 16;
     constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
@@ -106,10 +114,18 @@ __device__ __forceinline__ void evict_row(const razor_head_desc &e, int head, in
             x[4] = __uint_as_float(old.z << 16); x[5] = __uint_as_float(old.z & 0xffff0000u);
             x[6] = __uint_as_float(old.w << 16); x[7] = __uint_as_float(old.w & 0xffff0000u);
         }
-        float *c = comp + ((size_t)head * 2 + which) * D + piece * NE;
+        const size_t at = ((size_t)head * 2 + which) * D + piece * NE;
+        float *hi = comp + at, *lo = comp_lo + at;
         const float inv = 1.f / (float)(e.n_dropped + 1);
 #pragma unroll
-        for (int k = 0; k < NE; ++k) c[k] += (x[k] - c[k]) * inv;
+        for (int k = 0; k < NE; ++k) {
+            const float h = hi[k], l = lo[k];
+            const float y = ((x[k] - h) - l) * inv + l;   // increment plus what earlier additions lost
+            const float t = h + y;
+            const float bb = t - h;
+            lo[k] = (h - (t - bb)) + (y - bb);            // h + y = t + this, exactly
+            hi[k] = t;
+        }
         *reinterpret_cast<uint4 *>(pos) =
             *reinterpret_cast<const uint4 *>((which ? v_new : k_new) + (int64_t)head * RB + piece * 16);
     }
@@ -232,7 +248,7 @@ __global__ __launch_bounds__(256, 2) void decode_partial_bf16_kernel(
             const bool slides = count.slides(e.rows, e.flags, e.window);
             const int slot = slides ? n_sink + e.evicted % e.window : e.rows;
             if ((slides || rows > e.rows) && slot / kBlockRows >= lo - first && slot / kBlockRows < seg_end - first) {
-                if (slides) evict_row<RB, RAZOR_BF16>(e, i, slot, kplane, vplane, k_new, v_new, comp, lane);
+                if (slides) evict_row<RB, RAZOR_BF16>(e, i, slot, kplane, vplane, k_new, v_new, comp, comp + (size_t)n_heads * 2 * D, lane);
                 else append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
             }
         }
@@ -450,7 +466,7 @@ __global__ __launch_bounds__(256, 1) void decode_partial_f32_kernel(
             const bool slides = count.slides(e.rows, e.flags, e.window);
             const int slot = slides ? n_sink + e.evicted % e.window : e.rows;
             if ((slides || rows > e.rows) && slot / kBlockRows >= lo - first && slot / kBlockRows < seg_end - first) {
-                if (slides) evict_row<RB, RAZOR_F32>(e, i, slot, kplane, vplane, k_new, v_new, comp, lane);
+                if (slides) evict_row<RB, RAZOR_F32>(e, i, slot, kplane, vplane, k_new, v_new, comp, comp + (size_t)n_heads * 2 * D, lane);
                 else append_row<RB>(e, i, kplane, vplane, k_new, v_new, lane);
             }
         }
@@ -704,24 +720,23 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
 
 thread_local hipEvent_t g_profile_start = nullptr, g_profile_stop = nullptr;
 
-}  // namespace
-}  // namespace razor
-
-extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const void *k_new,
-                                 const void *v_new, void *arena, float *comp,
-                                 razor_head_desc *desc_dev, void *O, void *workspace,
-                                 size_t workspace_bytes, void *stream)
+// Argument checks shared by the decode entry points (everything but the workspace).
+int check_decode_args(const razor_params *p, const void *Q, const void *k_new, const void *v_new,
+                      const void *arena, const float *comp, const razor_head_desc *desc_dev, const void *O)
 {
-    using namespace razor;
     if (check_params(p) != RAZOR_OK) return RAZOR_EINVAL;
-    if (!Q || !arena || !comp || !desc_dev || !O || !workspace) return RAZOR_EINVAL;
+    if (!Q || !arena || !comp || !desc_dev || !O) return RAZOR_EINVAL;
     if ((k_new == nullptr) != (v_new == nullptr)) return RAZOR_EINVAL;
-    if (((uintptr_t)Q | (uintptr_t)arena | (uintptr_t)comp | (uintptr_t)O | (uintptr_t)workspace |
+    if (((uintptr_t)Q | (uintptr_t)arena | (uintptr_t)comp | (uintptr_t)O | (uintptr_t)desc_dev |
          (uintptr_t)k_new | (uintptr_t)v_new) & 15)
         return RAZOR_EINVAL;
-    const DecodeWorkspace ws = decode_workspace(*p);
-    if (workspace_bytes < ws.bytes) return RAZOR_ECAPACITY;
+    if ((uintptr_t)p->alibi_slopes & 3) return RAZOR_EINVAL;
+    return RAZOR_OK;
+}
 
+// Wavefronts the streaming kernel is split over.
+int decode_workers(const razor_params *p, int *out)
+{
     int workers = p->n_workers;
     if (workers == 0) {
         int rc = auto_workers(&workers);
@@ -732,12 +747,19 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
         // row size is at its best with one).
         if (p->dtype == RAZOR_BF16 && p->head_dim == 64) workers *= 2;
     }
-    workers = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
+    *out = std::max(4, std::min(workers, RAZOR_MAX_WORKERS));
+    return RAZOR_OK;
+}
 
+// The two launches of a decode step; `scratch` holds the layout `ws`.
+int launch_decode(const razor_params *p, const void *Q, const void *k_new, const void *v_new, void *arena,
+                  float *comp, razor_head_desc *desc_dev, void *O, void *scratch, const DecodeWorkspace &ws,
+                  int workers, void *stream)
+{
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int n_heads = p->batch * p->n_kv_heads, g = p->n_q_heads / p->n_kv_heads;
     const int D = p->head_dim, has_new = k_new != nullptr;
-    char *wsb = static_cast<char *>(workspace);
+    char *wsb = static_cast<char *>(scratch);
     int32_t *prefix = reinterpret_cast<int32_t *>(wsb + ws.prefix_off);
     int32_t *nd = reinterpret_cast<int32_t *>(wsb + ws.nd_off);
     float *ml = reinterpret_cast<float *>(wsb + ws.ml_off);
@@ -783,6 +805,39 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
     RAZOR_HIP_CHECK(hipGetLastError());
     return RAZOR_OK;
 }
+
+}  // namespace
+}  // namespace razor
+
+extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const void *k_new,
+                                 const void *v_new, void *arena, float *comp,
+                                 razor_head_desc *desc_dev, void *O, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    using namespace razor;
+    int rc = check_decode_args(p, Q, k_new, v_new, arena, comp, desc_dev, O);
+    if (rc != RAZOR_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & 15)) return RAZOR_EINVAL;
+    const DecodeWorkspace ws = decode_workspace(*p);
+    if (workspace_bytes < ws.bytes)
+        return capacity_failure("razor_decode_attn: workspace smaller than razor_plan reported");
+    int workers = 0;
+    rc = decode_workers(p, &workers);
+    if (rc != RAZOR_OK) return rc;
+    return launch_decode(p, Q, k_new, v_new, arena, comp, desc_dev, O, workspace, ws, workers, stream);
+}
+
+#ifdef RAZOR_TIMELINE
+// Debug build only: byte offset inside the decode workspace of the per-wave clock stamps
+// (four int64 per wave: start, range located, end, head segments crossed).
+extern "C" RAZOR_API uint64_t razor_timeline_offset(const razor_params *p)
+{
+    using namespace razor;
+    if (check_params(p) != RAZOR_OK) return 0;
+    const int g = p->n_q_heads / p->n_kv_heads;
+    return decode_workspace(*p).acc_off + timeline_floats(p->batch * p->n_kv_heads, g, p->head_dim) * sizeof(float);
+}
+#endif
 
 extern "C" int razor_profile_events(void *ev_start, void *ev_stop)
 {

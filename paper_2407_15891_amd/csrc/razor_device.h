@@ -7,6 +7,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
+
 #include "razor_internal.h"
 
 namespace razor {
@@ -14,6 +16,18 @@ namespace razor {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// {rows, cap, n_dropped, flags} of a table entry travel as one aligned 128-bit load, the buffer
+// length as a separate word: the entry is 48 bytes and the table 16-byte aligned (checked by
+// every entry point that takes one).
+static_assert(sizeof(razor_head_desc) == 48, "table entries must keep 16-byte alignment");
+static_assert(offsetof(razor_head_desc, rows) == 16 && offsetof(razor_head_desc, cap) == 20 &&
+              offsetof(razor_head_desc, n_dropped) == 24 && offsetof(razor_head_desc, flags) == 28,
+              "desc_counts() reads these four as one int4");
+__device__ __forceinline__ int4 desc_counts(const razor_head_desc *__restrict__ desc, int idx)
+{
+    return *reinterpret_cast<const int4 *>(&desc[idx].rows);   // {rows, cap, n_dropped, flags}
+}
 
 // Cache and source rows are read once per pass and not again before everything else has
 // gone by: non-temporal loads keep them from displacing each other in L2 and measurably
@@ -57,17 +71,15 @@ struct CachedBlocks {   // rows held this decode step (the token being appended 
     }
     __device__ __forceinline__ int operator()(const razor_head_desc *__restrict__ desc, int idx) const
     {
-        const char *e = reinterpret_cast<const char *>(desc + idx);
-        const int4 f = *reinterpret_cast<const int4 *>(e + 16);   // {rows, cap, n_dropped, flags}
-        const int window = *reinterpret_cast<const int *>(e + 36);
+        const int4 f = desc_counts(desc, idx);
+        const int window = desc[idx].window;
         return (rows_of(f.x, f.y, (uint32_t)f.w, window) + kBlockRows - 1) / kBlockRows;
     }
     // N_d as it counts for this step (the row a sliding head evicts already included)
     __device__ __forceinline__ int step_n_dropped(const razor_head_desc *__restrict__ desc, int idx) const
     {
-        const char *e = reinterpret_cast<const char *>(desc + idx);
-        const int4 f = *reinterpret_cast<const int4 *>(e + 16);
-        const int window = *reinterpret_cast<const int *>(e + 36);
+        const int4 f = desc_counts(desc, idx);
+        const int window = desc[idx].window;
         return f.z + (slides(f.x, (uint32_t)f.w, window) ? 1 : 0);
     }
 };
@@ -85,8 +97,8 @@ template <class ROWS>
 struct RowSetBlocks {     // 16-row blocks of such a set
     __device__ __forceinline__ int operator()(const razor_head_desc *__restrict__ desc, int idx) const
     {
-        const int4 f = *reinterpret_cast<const int4 *>(reinterpret_cast<const char *>(desc + idx) + 16);
-        return (ROWS::n(f.x, f.z) + kBlockRows - 1) / kBlockRows;   // {rows, cap, n_dropped, flags}
+        const int4 f = desc_counts(desc, idx);
+        return (ROWS::n(f.x, f.z) + kBlockRows - 1) / kBlockRows;
     }
 };
 

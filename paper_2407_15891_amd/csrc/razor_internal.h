@@ -30,7 +30,9 @@ struct DecodeWorkspace {
     size_t bytes;
     int slots;
 };
-DecodeWorkspace decode_workspace(const razor_params &p);
+// `workers`: wavefronts the launch is split over; the caller-provided workspace is sized for the
+// largest count a launch may use.
+DecodeWorkspace decode_workspace(const razor_params &p, int workers = RAZOR_MAX_WORKERS);
 
 struct CompressWorkspace {
     size_t prefix_off;   // int32[n_heads + 2]: dropped-block prefix sums, then blocks-per-worker
@@ -53,6 +55,18 @@ int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *ma
 
 // Remembers `what` + the HIP error text for razor_strerror; returns RAZOR_EHIP.
 int hip_failure(const char *what, int hip_error);
+
+// Remembers which buffer was too small for razor_strerror; returns RAZOR_ECAPACITY.
+int capacity_failure(const char *what);
+
+#ifdef RAZOR_TIMELINE
+// Debug build: where the streaming waves leave their clock stamps, in floats from the start of
+// the partial outputs of the decode workspace.
+constexpr size_t timeline_floats(int n_heads, int g, int head_dim)
+{
+    return (size_t)(RAZOR_MAX_WORKERS / 2 + n_heads) * g * head_dim;
+}
+#endif
 
 }  // namespace razor
 #endif

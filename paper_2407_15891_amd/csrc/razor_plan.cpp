@@ -20,6 +20,14 @@ int hip_failure(const char *what, int hip_error)
     return RAZOR_EHIP;
 }
 
+static thread_local const char *g_capacity_text = "workspace too small";
+
+int capacity_failure(const char *what)
+{
+    g_capacity_text = what;   // string literals only
+    return RAZOR_ECAPACITY;
+}
+
 int check_params(const razor_params *p)
 {
     if (!p) return RAZOR_EINVAL;
@@ -33,7 +41,8 @@ int check_params(const razor_params *p)
     if (p->use_comp != 0 && p->use_comp != 1) return RAZOR_EINVAL;
     if (!(p->scale == p->scale) || p->scale <= 0.0f) return RAZOR_EINVAL;
     if (p->n_workers < 0 || p->n_workers > RAZOR_MAX_WORKERS) return RAZOR_EINVAL;
-    if ((int64_t)p->batch * p->n_kv_heads > (1 << 20)) return RAZOR_EINVAL;
+    // (sequence, KV head) pairs index gridDim.y of the compaction launches (limit 65535)
+    if ((int64_t)p->batch * p->n_kv_heads > RAZOR_MAX_HEADS) return RAZOR_EINVAL;
     if (p->sliding != 0 && p->sliding != 1) return RAZOR_EINVAL;
     if (p->reserved0 != 0) return RAZOR_EINVAL;
     for (int h = 0; h < p->n_kv_heads; ++h) {
@@ -44,13 +53,13 @@ int check_params(const razor_params *p)
     return RAZOR_OK;
 }
 
-DecodeWorkspace decode_workspace(const razor_params &p)
+DecodeWorkspace decode_workspace(const razor_params &p, int workers)
 {
     const size_t n_heads = (size_t)p.batch * p.n_kv_heads;
     const size_t g = (size_t)(p.n_q_heads / p.n_kv_heads);
     DecodeWorkspace w;
     // a (worker, head) segment owns slot worker + head, so slots <= workers + heads
-    w.slots = (int)(RAZOR_MAX_WORKERS + n_heads);
+    w.slots = (int)(workers + n_heads);
     w.prefix_off = 0;
     w.nd_off = round_up((n_heads + 2) * sizeof(int32_t), 256);
     w.ml_off = w.nd_off + round_up(n_heads * sizeof(int32_t), 256);
@@ -127,7 +136,8 @@ int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *ma
     }
     const size_t row_bytes = (size_t)2 * p.head_dim * elem_size(p.dtype);
     sizes.arena_bytes = (uint64_t)row_off * row_bytes;
-    sizes.comp_bytes = (uint64_t)n_heads * 2 * p.head_dim * sizeof(float);
+    // sliding mode carries every running mean as an fp32 pair: a second array of low-order parts
+    sizes.comp_bytes = (uint64_t)n_heads * 2 * p.head_dim * sizeof(float) * (p.sliding ? 2 : 1);
     sizes.desc_bytes = (uint64_t)n_heads * sizeof(razor_head_desc);
     sizes.kept_idx_bytes = (uint64_t)kept_off * sizeof(int32_t);
     const size_t group_bytes = (size_t)groups * 2 * p.head_dim * sizeof(float);
@@ -192,7 +202,7 @@ extern "C" const char *razor_strerror(int status)
     switch (status) {
     case RAZOR_OK: return "ok";
     case RAZOR_EINVAL: return "invalid argument";
-    case RAZOR_ECAPACITY: return "workspace too small";
+    case RAZOR_ECAPACITY: return razor::g_capacity_text;
     case RAZOR_EHIP: return razor::g_hip_error_text;
     default: return "unknown status";
     }

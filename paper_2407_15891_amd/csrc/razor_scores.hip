@@ -383,7 +383,8 @@ extern "C" int razor_head_scores(const void *Q, const void *K, int dtype, int n_
     if ((q_stride_n | q_stride_h | k_stride_n | k_stride_h) % 8) return RAZOR_EINVAL;   // 16-byte rows
     if (((uintptr_t)Q | (uintptr_t)K) & 15) return RAZOR_EINVAL;
     const size_t need = razor_head_scores_workspace(n_q_heads, n_tokens);
-    if (!workspace || workspace_bytes < need) return RAZOR_ECAPACITY;
+    if (!workspace || workspace_bytes < need)
+        return capacity_failure("razor_head_scores: workspace smaller than razor_head_scores_workspace reported");
 
     const int n_tiles = (n_tokens + kQueriesPerGroup - 1) / kQueriesPerGroup;
     const float scale_log2e = scale * 1.4426950408889634f;

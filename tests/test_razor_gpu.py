@@ -64,7 +64,7 @@ def make_pair(w, **kw):
 def check_compress(w, cache, oc, what, comp_atol=4e-6):
     desc = cache.desc()
     kept_dev = cache.kept_idx_dev.cpu().numpy()
-    comp = cache.comp.cpu().numpy().reshape(w.B, w.Hkv, 2, w.d).astype(np.float64)
+    comp = cache.comp_tokens().cpu().numpy().astype(np.float64)
     Kb, Vb = raw_bytes(w.K), raw_bytes(w.V)
     np.testing.assert_array_equal(desc, cache.desc_host)                      # device table == planned table
     scale_in = float(w.K.abs().max())
@@ -93,6 +93,25 @@ def run_steps(w, cache, oc, steps, what, append=True, use_comp=True, bf16_out=Fa
         e = check_output(out, ref, f"{what} step {t}", bf16_out)
         worst = (max(worst[0], e[0]), max(worst[1], e[1]))
     say(f"    {what}: {steps} step(s), max-abs {worst[0]:.2e}, row-rel {worst[1]:.2e}")
+
+
+def check_bf16_output(cache, Q, ref, what):
+    """The same step (no append) written out as bf16: the write-out rounds the fp32 result to
+    nearest even, so it must equal the fp32 output rounded by torch bit for bit, and it lies
+    within the arithmetic bar plus half a bf16 ulp (<= 2^-9 |ref| * 2) of the oracle."""
+    p = cache.params
+    out32 = torch.empty(p.batch, p.n_q_heads, p.head_dim, dtype=torch.float32, device=DEV)
+    out16 = torch.empty(p.batch, p.n_q_heads, p.head_dim, dtype=torch.bfloat16, device=DEV)
+    keep = p.out_dtype
+    try:
+        p.out_dtype = razor.RAZOR_F32
+        cache.decode(Q, out=out32)
+        p.out_dtype = razor.RAZOR_BF16
+        cache.decode(Q, out=out16)
+    finally:
+        p.out_dtype = keep
+    assert torch.equal(out16, out32.to(torch.bfloat16)), f"{what}: bf16 write-out is not the rounded fp32 result"
+    return check_output(out16, ref, f"{what} (bf16 output)", bf16_out=True)
 
 
 # ----------------------------------------------------------------- compress
@@ -135,6 +154,22 @@ def test_compress_from_column_sums(cfg, context, window, batch):
     # same bits on a second run (fixed summation order)
     again = cache.column_sums(w.K, w.V)
     assert torch.equal(again, sums)
+
+
+def test_compress_from_column_sums_when_no_row_is_kept():
+    """No sinks, no window, no retrieval head: every head is its compensation token alone.  Given
+    column sums nothing is copied at all and Eq.(4) is col_sums / N_d."""
+    say("compress from column sums, heads that keep no row")
+    w = make_workload(3, DEV, context=700, window=0, batch=2, max_new=2, mask=np.zeros(8, np.uint8))
+    w.n_sink = 0
+    cache = razor.RazorCache.from_workload(w, want_kept_idx=True)
+    assert (cache.desc_host["rows"] == 0).all()
+    sums = cache.column_sums(w.K, w.V)
+    cache.compress(w.K, w.V, col_sums=sums)
+    oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, 0, 0, max_new=2)
+    check_compress(w, cache, oc, "no kept rows, column sums", comp_atol=2e-5)
+    run_steps(w, cache, oc, 1, "no kept rows", append=False)
+    run_steps(w, cache, oc, 2, "no kept rows + appended")
 
 
 def test_compress_strided_input_and_fp32_dim128():
@@ -281,6 +316,9 @@ def test_full_size_config2():
     cache, oc = make_pair(w)
     check_compress(w, cache, oc, "config 2")
     run_steps(w, cache, oc, w.decode_steps, "config 2")
+    Q, _, _ = w.step_inputs(1000, append=False)
+    e = check_bf16_output(cache, Q, oc.decode(Q.cpu(), w.scale), "config 2")
+    say(f"    config 2 bf16 output: max-abs {e[0]:.2e}, row-rel {e[1]:.2e}")
 
 
 def test_full_size_config3():
@@ -291,7 +329,7 @@ def test_full_size_config3():
     desc = cache.desc()
     np.testing.assert_array_equal(desc["rows"], oc.rows().reshape(-1))
     np.testing.assert_array_equal(desc["n_dropped"], oc.N_d.reshape(-1))
-    comp = cache.comp.cpu().numpy().reshape(w.B, w.Hkv, 2, w.d).astype(np.float64)
+    comp = cache.comp_tokens().cpu().numpy().astype(np.float64)
     np.testing.assert_allclose(comp[:, :, 0], oc.khat, rtol=0, atol=3e-5)
     np.testing.assert_allclose(comp[:, :, 1], oc.vhat, rtol=0, atol=3e-5)
     # sampled heads: copied bits
@@ -302,6 +340,9 @@ def test_full_size_config3():
         np.testing.assert_array_equal(v, Vb[0, h][oc.kept_of(0, h)])
     run_steps(w, cache, oc, 1, "config 3", append=False)
     run_steps(w, cache, oc, 1, "config 3 append")
+    Q, _, _ = w.step_inputs(1000, append=False)
+    e = check_bf16_output(cache, Q, oc.decode(Q.cpu(), w.scale), "config 3")
+    say(f"    config 3 bf16 output: max-abs {e[0]:.2e}, row-rel {e[1]:.2e}")
 
 
 def test_full_size_config4():
@@ -311,7 +352,17 @@ def test_full_size_config4():
     desc = cache.desc()
     np.testing.assert_array_equal(desc["rows"], oc.rows().reshape(-1))
     np.testing.assert_array_equal(desc["n_dropped"], oc.N_d.reshape(-1))
+    # copied bits of the shortest, the longest and two more sequences (every KV head of each)
+    order = np.argsort(w.seq_lens)
+    for b in (int(order[0]), int(order[-1]), int(order[5]), int(order[10])):
+        Kb, Vb = raw_bytes(w.K[b:b + 1]), raw_bytes(w.V[b:b + 1])
+        for h in range(w.Hkv):
+            k, v = arena_rows(cache, desc, b * w.Hkv + h)
+            np.testing.assert_array_equal(k, Kb[0, h][oc.kept_of(b, h)])
+            np.testing.assert_array_equal(v, Vb[0, h][oc.kept_of(b, h)])
     run_steps(w, cache, oc, 1, "config 4")
+    Q, _, _ = w.step_inputs(1000, append=False)
+    check_bf16_output(cache, Q, oc.decode(Q.cpu(), w.scale), "config 4")
 
 
 def test_full_size_config5_sampled_layers():
@@ -332,12 +383,20 @@ def test_full_size_config5_sampled_layers():
         cache = razor.RazorCache.from_workload(w)
         cache.compress(w.K, w.V)
         oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, w.n_sink, w.window, max_new=256)
+        w_K0, w_V0 = w.K[:1].cpu(), w.V[:1].cpu()
         w.K = w.V = None
         say(f"    layer {layer}: compressed, oracle cache built")
         np.testing.assert_array_equal(cache.desc()["n_dropped"], oc.N_d.reshape(-1))
-        comp = cache.comp.cpu().numpy().reshape(w.B, w.Hkv, 2, w.d).astype(np.float64)
+        comp = cache.comp_tokens().cpu().numpy().astype(np.float64)
         np.testing.assert_allclose(comp[:, :, 0], oc.khat, rtol=0, atol=3e-5)
         np.testing.assert_allclose(comp[:, :, 1], oc.vhat, rtol=0, atol=3e-5)
+        desc = cache.desc()
+        Kb, Vb = raw_bytes(w_K0), raw_bytes(w_V0)            # copied bits of sequence 0, every KV head
+        for h in range(w.Hkv):
+            k, v = arena_rows(cache, desc, h)
+            np.testing.assert_array_equal(k, Kb[0, h][oc.kept_of(0, h)])
+            np.testing.assert_array_equal(v, Vb[0, h][oc.kept_of(0, h)])
+        del Kb, Vb, w_K0, w_V0
         worst = (0.0, 0.0)
         for t in range(256):
             Q, k, v = w.step_inputs(t)
@@ -376,7 +435,7 @@ def test_sliding_mode_parity(cfg, context, window, batch, workers, steps):
             d = cache.desc()
             np.testing.assert_array_equal(d["rows"], oc.rows().reshape(-1))
             np.testing.assert_array_equal(d["n_dropped"], oc.N_d.reshape(-1))
-            comp = cache.comp.cpu().numpy().reshape(w.B, w.Hkv, 2, w.d).astype(np.float64)
+            comp = cache.comp_tokens().cpu().numpy().astype(np.float64)
             tol = 1e-5 * float(w.K.abs().max())
             np.testing.assert_allclose(comp[:, :, 0], oc.khat, rtol=0, atol=tol)
             np.testing.assert_allclose(comp[:, :, 1], oc.vhat, rtol=0, atol=tol)
@@ -384,6 +443,56 @@ def test_sliding_mode_parity(cfg, context, window, batch, workers, steps):
     nonret = np.tile(w.mask == 0, w.B)
     assert (d["rows"][nonret] <= w.n_sink + w.window).all() and not (d["flags"] & razor.RAZOR_HEAD_OVERFLOW).any()
     say(f"    {steps} steps: max-abs {worst[0]:.2e}, row-rel {worst[1]:.2e}, evicted up to {int(d['evicted'].max())}")
+
+
+@pytest.mark.parametrize("cfg,context,window,batch,steps", [
+    (3, 600, 48, 2, 20000),      # bf16 GQA: the 48-row ring wraps 400 times, N_d grows from 548 to 20548
+    (1, 500, 40, 1, 20000),      # fp32 MHA
+])
+def test_sliding_mode_long_generation(cfg, context, window, batch, steps):
+    """Sliding mode exists for generations of any length: 20 000 steps on a small shape, the oracle
+    (Eq.(4) from scratch in fp64 over everything dropped so far) checked at ten steps including the
+    last.  K and V carry a constant offset so that the means are of order one and their fp32
+    rounding would show: the running means must stay within 4 ulp of the fp64 means (a plain fp32
+    update is off by tens of ulp by then), outputs within the usual bars."""
+    say(f"sliding long generation cfg={cfg} context={context} window={window} batch={batch} steps={steps}")
+    w = make_workload(cfg, DEV, context=context, window=window, batch=batch, max_new=steps)
+    w.K += 1.5
+    w.V -= 2.0
+    cache = razor.RazorCache.from_workload(w, sliding=True)
+    cache.compress(w.K, w.V)
+    oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, w.n_sink, w.window, max_new=steps, sliding=True)
+    gen = torch.Generator(device=DEV); gen.manual_seed(31337 + cfg)
+    check_at = sorted(set(int(x) for x in np.linspace(0, steps - 1, 10)))
+    chunk, worst, worst_ulp = 2000, (0.0, 0.0), 0.0
+    out = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=DEV)
+    for t0 in range(0, steps, chunk):
+        n = min(chunk, steps - t0)
+        Qs = torch.randn(n, w.B, w.Hq, w.d, generator=gen, device=DEV).to(w.dtype)
+        ks = (torch.randn(n, w.B, w.Hkv, w.d, generator=gen, device=DEV) + 1.5).to(w.dtype)
+        vs = (torch.randn(n, w.B, w.Hkv, w.d, generator=gen, device=DEV) - 2.0).to(w.dtype)
+        ks_c, vs_c = ks.cpu(), vs.cpu()
+        for j in range(n):
+            t = t0 + j
+            cache.decode(Qs[j], ks[j], vs[j], out=out)
+            oc.append(ks_c[j], vs_c[j])
+            if t in check_at:
+                e = check_output(out, oc.decode(Qs[j].cpu(), w.scale), f"long sliding step {t}")
+                worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+                d = cache.desc()
+                np.testing.assert_array_equal(d["rows"], oc.rows().reshape(-1))
+                np.testing.assert_array_equal(d["n_dropped"], oc.N_d.reshape(-1))
+                comp = cache.comp_tokens().cpu().numpy().astype(np.float64)
+                for got, ref in ((comp[:, :, 0], oc.khat), (comp[:, :, 1], oc.vhat)):
+                    ulp = np.spacing(np.abs(ref).astype(np.float32)).astype(np.float64)
+                    worst_ulp = max(worst_ulp, float((np.abs(got - ref) / ulp).max()))
+                    # the prefill part of each mean comes from the compression pass (fp32 partial sums: a few
+                    # 1e-7 relative to max|x|); the decode-time updates add at most an ulp on top
+                    assert (np.abs(got - ref) <= 4 * ulp + 4e-7 * 6.0).all(), f"step {t}: mean off by {worst_ulp:.1f} ulp"
+        say(f"    through step {t0 + n - 1}: max-abs {worst[0]:.2e}, row-rel {worst[1]:.2e}, means within {worst_ulp:.1f} ulp")
+    d = cache.desc()
+    nonret = np.tile(w.mask == 0, w.B)
+    assert (d["rows"][nonret] == w.n_sink + w.window).all() and (d["evicted"][nonret] == steps).all()
 
 
 def test_sliding_mode_without_compensation_is_sinks_plus_window():
@@ -523,7 +632,7 @@ def test_many_heads():
                              retrieval_mask=mask, n_sink=2, window=20, max_new=3, dtype=torch.bfloat16, device=DEV)
     cache.compress(K, V)
     oc = orc.OracleCache(K.cpu(), V.cpu(), seq, mask, 2, 20, max_new=3)
-    comp = cache.comp.cpu().numpy().reshape(B, Hkv, 2, d).astype(np.float64)
+    comp = cache.comp_tokens().cpu().numpy().astype(np.float64)
     np.testing.assert_allclose(comp[:, :, 0], oc.khat, rtol=0, atol=2e-5)
     for t in range(3):
         Q = torch.randn(B, Hkv * g, d, generator=gen, device=DEV).to(torch.bfloat16)
@@ -541,9 +650,22 @@ def test_read_stream_probe_runs_on_odd_sizes():
     buf = torch.ones(5 * 4096 * 1031 + 777, dtype=torch.uint8, device=DEV)
     sink = torch.zeros(4 * razor.RAZOR_MAX_WORKERS, dtype=torch.uint8, device=DEV)
     for nbytes, workers in ((4096, 0), (4096 * 3 + 5, 4), (buf.numel(), 0), (buf.numel(), 1000), (buf.numel(), 8192)):
-        assert razor.razor_probe_read_stream(buf, nbytes, workers, sink) == razor.RAZOR_OK
+        for pattern in (razor.RAZOR_PROBE_CONTIGUOUS, razor.RAZOR_PROBE_INTERLEAVED):
+            for depth, nt in ((1, 1), (2, 0), (4, 1), (8, 0)):
+                assert razor.razor_probe_read_stream(buf, nbytes, workers, pattern, depth, nt, sink) == razor.RAZOR_OK
     torch.cuda.synchronize()
     assert int(sink.sum()) == 0          # the sink is only written if a checksum hits one value in 2^32
+
+
+def test_copy_probe_copies_whole_pieces_and_nothing_else():
+    src = torch.randint(0, 255, (4096 * 517 + 100,), dtype=torch.uint8, device=DEV)
+    for workers in (0, 4, 1000, 8192):
+        for pattern in (razor.RAZOR_PROBE_CONTIGUOUS, razor.RAZOR_PROBE_INTERLEAVED):
+            for hints in range(4):
+                dst = torch.zeros_like(src)
+                assert razor.razor_probe_copy(dst, src, src.numel(), workers, pattern, hints) == razor.RAZOR_OK
+                n = src.numel() // 4096 * 4096
+                assert torch.equal(dst[:n], src[:n]) and int(dst[n:].sum()) == 0
 
 
 @pytest.mark.parametrize("seed", list(range(24)))
@@ -582,6 +704,7 @@ def test_random_shapes_parity(seed):
         out = cache.decode(Q, k, v)
         oc.append(k.cpu(), v.cpu())
         check_output(out, oc.decode(Q.cpu(), d ** -0.5, use_comp=use_comp), f"seed {seed} step {t}")
+    check_bf16_output(cache, Q, oc.decode(Q.cpu(), d ** -0.5, use_comp=use_comp), f"seed {seed}")
     dsc = cache.desc()
     np.testing.assert_array_equal(dsc["rows"], oc.rows().reshape(-1))
     np.testing.assert_array_equal(dsc["n_dropped"], oc.N_d.reshape(-1))

@@ -37,15 +37,17 @@ def plan(p, seq_lens, mask, want_idx=True):
 
 def test_library_exports_every_declared_symbol():
     lib = razor.load_library()
-    header = open(os.path.join(ROOT, "include", "razor.h")).read()
-    declared = set(re.findall(r"\b(razor_[a-z_]+)\s*\(", header))
-    assert declared == set(razor.EXPORTS)
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):       # razor.h and razor_bench.h
+        header = open(os.path.join(ROOT, "include", name)).read()
+        declared |= set(re.findall(r"^RAZOR_API [^;]*?\b(razor_[a-z_]+)\s*\(", header, re.M | re.S))
+    assert len(declared) == 11 and declared == set(razor.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
     assert razor.razor_strerror(razor.RAZOR_OK) == "ok"
     assert "invalid" in razor.razor_strerror(razor.RAZOR_EINVAL)
     assert "workspace" in razor.razor_strerror(razor.RAZOR_ECAPACITY)
-    assert ctypes.sizeof(razor.RazorHeadDesc) == 40 and ctypes.sizeof(razor.RazorParams) == 72
+    assert ctypes.sizeof(razor.RazorHeadDesc) == 48 and ctypes.sizeof(razor.RazorParams) == 72
 
 
 @pytest.mark.parametrize("seq_lens,mask,n_sink,window", [
@@ -81,7 +83,7 @@ def test_plan_matches_oracle_table(seq_lens, mask, n_sink, window):
         off += e["cap"]
     assert sizes.total_cap == off
     assert sizes.arena_bytes == off * 2 * p.head_dim * 2
-    assert sizes.comp_bytes == B * H * 2 * p.head_dim * 4 and sizes.desc_bytes == B * H * 40
+    assert sizes.comp_bytes == B * H * 2 * p.head_dim * 4 and sizes.desc_bytes == B * H * 48
     assert sizes.kept_idx_bytes == 4 * total and sizes.workspace_bytes > 0
 
 
@@ -139,6 +141,29 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert L.razor_decode_attn(pp, None, None, None, fake, fake, fake, fake, fake, 1 << 30, None) == razor.RAZOR_EINVAL
     # k_new without v_new
     assert L.razor_decode_attn(pp, fake, fake, None, fake, fake, fake, fake, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+    # a descriptor table that is not 16-byte aligned (its entries are fetched with 128-bit loads)
+    assert L.razor_decode_attn(pp, fake, None, None, fake, fake, fake + 8, fake, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+    assert L.razor_compress(pp, fake, fake, 4 * 100 * 128, 100 * 128, 128, seq.ctypes.data, mask.ctypes.data, fake,
+                            fake, fake + 8, None, None, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+
+
+def test_more_heads_than_a_launch_can_index_are_rejected_up_front():
+    """(sequence, KV head) pairs index one grid dimension of the compaction launches (limit 65535):
+    a call beyond that must fail in validation, not at a launch after other work was enqueued."""
+    ok = params(batch=65535 // 8, n_kv_heads=8, n_q_heads=8)
+    bad = params(batch=70000 // 8, n_kv_heads=8, n_q_heads=8)             # 70 000 pairs
+    sizes = razor.RazorSizes()
+    mask = np.zeros(8, np.uint8)
+    assert razor.razor_plan(ok, np.full(ok.batch, 40, np.int32), mask, None, None, sizes) == razor.RAZOR_OK
+    seq = np.full(bad.batch, 40, np.int32)
+    assert razor.razor_plan(bad, seq, mask, None, None, sizes) == razor.RAZOR_EINVAL
+    L = razor.load_library()
+    fake, pp = 4096, ctypes.byref(bad)
+    assert L.razor_compress(pp, fake, fake, 8 * 40 * 128, 40 * 128, 128, seq.ctypes.data, mask.ctypes.data, fake,
+                            fake, fake, None, None, fake, 1 << 40, None) == razor.RAZOR_EINVAL
+    assert L.razor_column_sums(pp, fake, fake, 8 * 40 * 128, 40 * 128, 128, seq.ctypes.data, fake, fake, 1 << 40,
+                               None) == razor.RAZOR_EINVAL
+    assert L.razor_decode_attn(pp, fake, None, None, fake, fake, fake, fake, fake, 1 << 40, None) == razor.RAZOR_EINVAL
 
 
 def test_missing_library_fails_loudly(monkeypatch):
@@ -266,8 +291,16 @@ def test_head_scores_arguments_are_checked_before_any_gpu_work():
 def test_read_stream_probe_arguments_are_checked():
     L = razor.load_library()
     fake = ctypes.c_void_p(0x1000)
-    assert L.razor_probe_read_stream(None, 1 << 20, 0, fake, None) == razor.RAZOR_EINVAL
-    assert L.razor_probe_read_stream(fake, 1 << 20, 0, None, None) == razor.RAZOR_EINVAL
-    assert L.razor_probe_read_stream(ctypes.c_void_p(0x1004), 1 << 20, 0, fake, None) == razor.RAZOR_EINVAL
-    assert L.razor_probe_read_stream(fake, 100, 0, fake, None) == razor.RAZOR_EINVAL        # less than one piece
-    assert L.razor_probe_read_stream(fake, 1 << 20, -3, fake, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_read_stream(None, 1 << 20, 0, 0, 2, 1, fake, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_read_stream(fake, 1 << 20, 0, 0, 2, 1, None, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_read_stream(ctypes.c_void_p(0x1004), 1 << 20, 0, 0, 2, 1, fake, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_read_stream(fake, 100, 0, 0, 2, 1, fake, None) == razor.RAZOR_EINVAL     # less than one piece
+    assert L.razor_probe_read_stream(fake, 1 << 20, -3, 0, 2, 1, fake, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_read_stream(fake, 1 << 20, 0, 2, 2, 1, fake, None) == razor.RAZOR_EINVAL  # unknown pattern
+    assert L.razor_probe_read_stream(fake, 1 << 20, 0, 0, 3, 1, fake, None) == razor.RAZOR_EINVAL  # unsupported depth
+    far = ctypes.c_void_p(0x10000000)
+    assert L.razor_probe_copy(None, fake, 1 << 20, 0, 0, 3, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_copy(far, ctypes.c_void_p(0x1008), 1 << 20, 0, 0, 3, None) == razor.RAZOR_EINVAL
+    assert L.razor_probe_copy(fake, ctypes.c_void_p(0x2000), 1 << 20, 0, 0, 3, None) == razor.RAZOR_EINVAL   # overlap
+    assert L.razor_probe_copy(far, fake, 1 << 20, 0, 0, 4, None) == razor.RAZOR_EINVAL             # unknown hint bits
+    assert L.razor_probe_copy(far, fake, 100, 0, 0, 3, None) == razor.RAZOR_EINVAL
