@@ -24,17 +24,19 @@ extern "C" {
  */
 RAZOR_API int razor_profile_events(void *ev_start, void *ev_stop);
 
-/* How a probe kernel hands 4 KB pieces to its wavefronts. */
-#define RAZOR_PROBE_CONTIGUOUS 0  /* wavefront w gets one contiguous range (the streaming kernels' pattern) */
-#define RAZOR_PROBE_INTERLEAVED 1 /* wavefront w gets pieces w, w + W, w + 2W, ...: at any moment the
-                                     chip works inside one moving window of the buffer                      */
+/* How a probe kernel hands 4 KB pieces to its W wavefronts (`pattern`): 0 = wavefront w gets one
+ * contiguous range; n >= 1 (at most 65536) = the buffer is cut into chunks of n pieces and wavefront
+ * w gets chunks w, w + W, w + 2W, ..., so that at any moment the chip works inside one moving window
+ * of W * n pieces. */
+#define RAZOR_PROBE_CONTIGUOUS 0
+#define RAZOR_PROBE_INTERLEAVED 1
 
 /*
  * Read-stream probe.  Reads the first bytes / 4096 * 4096 bytes at buf (device, 16-byte aligned,
  * at least 4096 bytes) exactly once with 128-bit loads and does no other work, so the duration
  * of this launch is what the device gives a kernel that only reads.
  *   n_workers    wavefronts; 0 = four per compute unit (one per SIMD); at most RAZOR_MAX_WORKERS
- *   pattern      RAZOR_PROBE_CONTIGUOUS or RAZOR_PROBE_INTERLEAVED
+ *   pattern      RAZOR_PROBE_CONTIGUOUS, RAZOR_PROBE_INTERLEAVED, or a chunk length in pieces (see above)
  *   depth        4 KB pieces a wavefront keeps in flight: 1, 2, 4 or 8
  *   nontemporal  non-zero: non-temporal loads (what the streaming kernels use)
  *   sink         device, at least 4 * RAZOR_MAX_WORKERS bytes, may be written (keeps the loads alive)

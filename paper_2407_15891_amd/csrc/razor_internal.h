@@ -11,10 +11,15 @@
 namespace razor {
 
 constexpr int kBlockRows = RAZOR_BLOCK_ROWS;  // K rows per arena block
-// razor_compress given column sums: the compaction kernel also adds up the kept rows of the heads
-// that dropped something, one partial sum per workgroup (kGroupBlocks 16-row blocks); they live
-// behind the rest of the compress workspace.
+// razor_compress: a copy workgroup moves kGroupBlocks 16-row blocks of a head, a summing
+// workgroup adds up kSumBlocks blocks of its dropped rows.  Each summing workgroup (and, when the
+// caller brings column sums, each copy workgroup of a head that dropped rows) leaves one partial
+// column sum behind the fixed part of the compress workspace.
 constexpr int kGroupBlocks = 4;
+#ifndef RAZOR_SUM_BLOCKS
+#define RAZOR_SUM_BLOCKS 32
+#endif
+constexpr int kSumBlocks = RAZOR_SUM_BLOCKS;
 constexpr int kMinBlocksPerWorker = 2;        // never split a decode finer than this
 
 inline int elem_size(int dtype) { return dtype == RAZOR_F32 ? 4 : 2; }
@@ -35,8 +40,9 @@ struct DecodeWorkspace {
 DecodeWorkspace decode_workspace(const razor_params &p, int workers = RAZOR_MAX_WORKERS);
 
 struct CompressWorkspace {
-    size_t prefix_off;   // int32[n_heads + 2]: dropped-block prefix sums, then blocks-per-worker
-    size_t partial_off;  // float[slots][2][head_dim]: column sums per (worker, head) segment
+    size_t prefix_off;   // int32[n_heads + 2]: first partial sum of every head (razor_compress), or block
+                         // prefix sums and blocks per worker (razor_column_sums)
+    size_t partial_off;  // float[slots][2][head_dim]: column sums per (worker, head) segment (razor_column_sums)
     size_t desc_off;     // razor_head_desc[n_heads]: private table of razor_column_sums
     size_t bytes;
 };
@@ -51,7 +57,7 @@ int check_params(const razor_params *p);
 // Fills desc (size batch * n_kv_heads); returns RAZOR_OK / RAZOR_EINVAL.
 int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *mask,
                std::vector<razor_head_desc> &desc, razor_sizes &sizes, int &max_dropped,
-               size_t *group_sum_bytes = nullptr);
+               size_t *partial_sum_bytes = nullptr);
 
 // Remembers `what` + the HIP error text for razor_strerror; returns RAZOR_EHIP.
 int hip_failure(const char *what, int hip_error);

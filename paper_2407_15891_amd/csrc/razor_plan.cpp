@@ -98,11 +98,11 @@ int auto_workers(int *out)
 
 int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *mask,
                std::vector<razor_head_desc> &desc, razor_sizes &sizes, int &max_dropped,
-               size_t *group_sum_bytes)
+               size_t *partial_sum_bytes)
 {
     const int n_heads = p.batch * p.n_kv_heads;
     desc.assign((size_t)n_heads, razor_head_desc{});
-    int64_t row_off = 0, kept_off = 0, groups = 0;
+    int64_t row_off = 0, kept_off = 0, groups = 0, chunks = 0;
     max_dropped = 0;
     for (int b = 0; b < p.batch; ++b) {
         const int64_t N = seq_lens[b];
@@ -129,7 +129,10 @@ int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *ma
             e.window = (int32_t)window;
             e.flags = (retrieval ? RAZOR_HEAD_RETRIEVAL : 0u) | (drops ? RAZOR_HEAD_COMP : 0u);
             if (e.n_dropped > max_dropped) max_dropped = e.n_dropped;
-            if (drops) groups += ((rows + kBlockRows - 1) / kBlockRows + kGroupBlocks - 1) / kGroupBlocks;
+            if (drops) {   // partial column sums razor_compress may leave: per copy group, or per chunk of dropped rows
+                groups += ((rows + kBlockRows - 1) / kBlockRows + kGroupBlocks - 1) / kGroupBlocks;
+                chunks += ((N - rows + kBlockRows - 1) / kBlockRows + kSumBlocks - 1) / kSumBlocks;
+            }
             row_off += cap;
             kept_off += rows;
         }
@@ -140,8 +143,8 @@ int build_plan(const razor_params &p, const int32_t *seq_lens, const uint8_t *ma
     sizes.comp_bytes = (uint64_t)n_heads * 2 * p.head_dim * sizeof(float) * (p.sliding ? 2 : 1);
     sizes.desc_bytes = (uint64_t)n_heads * sizeof(razor_head_desc);
     sizes.kept_idx_bytes = (uint64_t)kept_off * sizeof(int32_t);
-    const size_t group_bytes = (size_t)groups * 2 * p.head_dim * sizeof(float);
-    if (group_sum_bytes) *group_sum_bytes = group_bytes;
+    const size_t group_bytes = (size_t)std::max(groups, chunks + n_heads) * 2 * p.head_dim * sizeof(float);
+    if (partial_sum_bytes) *partial_sum_bytes = group_bytes;
     const size_t wd = decode_workspace(p).bytes, wc = compress_workspace(p).bytes + group_bytes;
     sizes.workspace_bytes = round_up(wd > wc ? wd : wc, 256);
     sizes.total_rows = kept_off;

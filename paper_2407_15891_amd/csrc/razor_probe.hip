@@ -29,19 +29,27 @@ __device__ __forceinline__ void probe_store(u32x4 *p, const u32x4 v)
     else *p = v;
 }
 
-// Piece k of wavefront w: its own contiguous range [w * per, ...), or every n_waves-th piece.
+// Piece k of wavefront w: its own contiguous range [w * per, ...), or -- interleaved in chunks of
+// `chunk` pieces -- the pieces of chunks w, w + n_waves, w + 2 n_waves, ...
 struct PieceMap {
     int64_t n_pieces, per, n_waves;
-    int interleaved;
+    int chunk;   // 0: contiguous
     __device__ __forceinline__ int64_t count(int64_t w) const
     {
-        if (interleaved) return w < n_pieces ? (n_pieces - w + n_waves - 1) / n_waves : 0;
+        if (chunk) {
+            const int64_t n_chunks = (n_pieces + chunk - 1) / chunk;
+            if (w >= n_chunks) return 0;
+            const int64_t mine = (n_chunks - w + n_waves - 1) / n_waves;             // chunks of this wave
+            const int64_t last = w + (mine - 1) * n_waves;                            // its last chunk
+            const int64_t tail = last == n_chunks - 1 ? n_pieces - last * chunk : chunk;   // pieces in it
+            return (mine - 1) * chunk + tail;
+        }
         const int64_t lo = w * per, hi = lo + per < n_pieces ? lo + per : n_pieces;
         return hi > lo ? hi - lo : 0;
     }
     __device__ __forceinline__ int64_t piece(int64_t w, int64_t k) const
     {
-        return interleaved ? w + k * n_waves : w * per + k;
+        return chunk ? (w + k / chunk * n_waves) * chunk + k % chunk : w * per + k;
     }
 };
 
@@ -103,7 +111,7 @@ __global__ __launch_bounds__(256) void copy_stream_kernel(u32x4 *__restrict__ ds
 int probe_setup(size_t bytes, int n_workers, int pattern, int &workers, PieceMap &map)
 {
     if (bytes < (size_t)kPieceBytes || n_workers < 0 || n_workers > RAZOR_MAX_WORKERS) return RAZOR_EINVAL;
-    if (pattern != RAZOR_PROBE_CONTIGUOUS && pattern != RAZOR_PROBE_INTERLEAVED) return RAZOR_EINVAL;
+    if (pattern < 0 || pattern > 65536) return RAZOR_EINVAL;
     workers = n_workers;
     if (workers == 0) {
         const int rc = auto_workers(&workers);
@@ -113,7 +121,7 @@ int probe_setup(size_t bytes, int n_workers, int pattern, int &workers, PieceMap
     map.n_pieces = (int64_t)(bytes / kPieceBytes);        // a tail shorter than a piece is not touched
     map.per = (map.n_pieces + workers - 1) / workers;
     map.n_waves = workers;
-    map.interleaved = pattern == RAZOR_PROBE_INTERLEAVED;
+    map.chunk = pattern;
     return RAZOR_OK;
 }
 
