@@ -20,8 +20,9 @@
  *   - The library owns no memory and keeps no state between calls.  The caller
  *     allocates every buffer with the sizes razor_plan reports.  Device calls
  *     only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
- *     default stream); they never allocate, never synchronise.  One exception,
- *     opt-in: the measurement hooks of razor_bench.h keep per-thread state.
+ *     default stream); they never allocate, never synchronise.  Two exceptions, both
+ *     opt-in: razor_decode_attn_static works in a fixed device array owned by the
+ *     library, and the measurement hooks of razor_bench.h keep per-thread state.
  *   - All functions return RAZOR_OK (0) or a negative razor_status.  Arguments
  *     are validated on the host before anything is enqueued; a failing call
  *     enqueues nothing.
@@ -199,6 +200,28 @@ RAZOR_API int razor_decode_attn(const razor_params *p, const void *Q, const void
                       const void *v_new, void *arena, float *comp,
                       razor_head_desc *desc_dev, void *O, void *workspace,
                       size_t workspace_bytes, void *stream);
+
+/*
+ * razor_decode_attn for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and same results as razor_decode_attn, but the split-K scratch of the
+ * step (block-prefix table, per-step N_d, partial softmax states) lives in a device array of
+ * RAZOR_STATIC_SCRATCH_BYTES that belongs to the library: every GPU the library runs on holds
+ * its own copy from the first call on that GPU until the process ends.  The call allocates
+ * nothing and frees nothing; its first call on a device only looks up the array's address.
+ * The scratch a step needs grows with the wavefronts it is split over (n_workers, or four per
+ * compute unit), the (sequence, KV head) pairs and the query group:
+ *   (workers + batch * n_kv_heads) * (n_q_heads / n_kv_heads) * (head_dim + 2) * 4 bytes + tables;
+ * a step that needs more than the array returns RAZOR_ECAPACITY and enqueues nothing (every
+ * benchmark configuration fits: at most 4.8 MB).  All calls on one GPU share that GPU's array,
+ * which keeps the last call's contents (nothing in it has to start at zero): calls that overlap
+ * in time on one GPU -- different streams, or different threads -- race; calls on one stream
+ * are safe.
+ */
+#define RAZOR_STATIC_SCRATCH_BYTES (8u << 20)
+RAZOR_API int razor_decode_attn_static(const razor_params *p, const void *Q, const void *k_new,
+                             const void *v_new, void *arena, float *comp,
+                             razor_head_desc *desc_dev, void *O, void *stream);
 
 /*
  * Sec. 3.3, identification of retrieval heads: echo and induction score of every query head

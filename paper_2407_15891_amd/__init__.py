@@ -1,7 +1,7 @@
 """Python binding of the razor C-ABI library (RazorAttention hot path on MI355X).
 
 The functions `razor_plan`, `razor_compress`, `razor_column_sums`, `razor_decode_attn`,
-`razor_head_scores`, `razor_head_scores_workspace`, `razor_select_heads`
+`razor_decode_attn_static`, `razor_head_scores`, `razor_head_scores_workspace`, `razor_select_heads`
 and `razor_strerror` carry the names and the argument order of `include/razor.h`
 (`razor_profile_events`, `razor_probe_read_stream`, `razor_probe_copy`: `include/razor_bench.h`); they only marshal
 arguments (torch tensors -> device pointers, numpy arrays -> host pointers).  Every
@@ -30,11 +30,12 @@ RAZOR_MAX_GROUP = 16
 RAZOR_MAX_WORKERS = 8192
 
 RAZOR_MAX_HEADS = 65535
+RAZOR_STATIC_SCRATCH_BYTES = 8 << 20
 RAZOR_PROBE_CONTIGUOUS, RAZOR_PROBE_INTERLEAVED = 0, 1
 
 # include/razor.h, then the measurement hooks of include/razor_bench.h
 EXPORTS = ("razor_plan", "razor_compress", "razor_column_sums", "razor_decode_attn",
-           "razor_head_scores_workspace", "razor_head_scores",
+           "razor_decode_attn_static", "razor_head_scores_workspace", "razor_head_scores",
            "razor_select_heads", "razor_strerror",
            "razor_profile_events", "razor_probe_read_stream", "razor_probe_copy")
 
@@ -99,6 +100,8 @@ def load_library():
     L.razor_column_sums.argtypes = [PP, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
     L.razor_decode_attn.restype = ctypes.c_int
     L.razor_decode_attn.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.razor_decode_attn_static.restype = ctypes.c_int
+    L.razor_decode_attn_static.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp, vp]
     ci = ctypes.c_int
     L.razor_head_scores_workspace.restype = sz
     L.razor_head_scores_workspace.argtypes = [ci, ci]
@@ -171,6 +174,13 @@ def razor_decode_attn(params: RazorParams, Q, k_new, v_new, arena, comp, desc_de
     return load_library().razor_decode_attn(
         ctypes.byref(params), _dev(Q), _dev(k_new), _dev(v_new), _dev(arena), _dev(comp),
         _dev(desc_dev), _dev(O), _dev(workspace), workspace_bytes, stream or None)
+
+
+def razor_decode_attn_static(params: RazorParams, Q, k_new, v_new, arena, comp, desc_dev, O,
+                             stream: int = 0) -> int:
+    return load_library().razor_decode_attn_static(
+        ctypes.byref(params), _dev(Q), _dev(k_new), _dev(v_new), _dev(arena), _dev(comp),
+        _dev(desc_dev), _dev(O), stream or None)
 
 
 def razor_head_scores_workspace(n_q_heads: int, n_tokens: int) -> int:

@@ -21,7 +21,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
+#include <mutex>
 #include <type_traits>
 
 #include "razor_bench.h"
@@ -751,7 +753,8 @@ int decode_workers(const razor_params *p, int *out)
     return RAZOR_OK;
 }
 
-// The two launches of a decode step; `scratch` holds the layout `ws`.
+// The two launches of a decode step; `scratch` holds the layout `ws` (caller's workspace or the
+// library's static array).
 int launch_decode(const razor_params *p, const void *Q, const void *k_new, const void *v_new, void *arena,
                   float *comp, razor_head_desc *desc_dev, void *O, void *scratch, const DecodeWorkspace &ws,
                   int workers, void *stream)
@@ -806,6 +809,38 @@ int launch_decode(const razor_params *p, const void *Q, const void *k_new, const
     return RAZOR_OK;
 }
 
+// ---------------------------------------------------------------- scratch owned by the library
+//
+// razor_decode_attn_static keeps the split-K scratch of a step (block-prefix table, per-step N_d,
+// partial softmax states) in this array instead of a caller-provided workspace.  Every device
+// the library runs on holds its own copy at its own address until the process ends; the host
+// learns that address once per device and passes it to the kernels like any other buffer.
+static __device__ __align__(256) unsigned char scratch[RAZOR_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device.
+int static_scratch(void **out)
+{
+    int dev = 0;
+    RAZOR_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return RAZOR_EINVAL;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        ptr = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!ptr) {
+            RAZOR_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+            if (!ptr) return hip_failure("hipGetSymbolAddress(scratch) returned NULL", (int)hipErrorInvalidSymbol);
+            g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+        }
+    }
+    *out = ptr;
+    return RAZOR_OK;
+}
+
 }  // namespace
 }  // namespace razor
 
@@ -825,6 +860,27 @@ extern "C" int razor_decode_attn(const razor_params *p, const void *Q, const voi
     rc = decode_workers(p, &workers);
     if (rc != RAZOR_OK) return rc;
     return launch_decode(p, Q, k_new, v_new, arena, comp, desc_dev, O, workspace, ws, workers, stream);
+}
+
+extern "C" int razor_decode_attn_static(const razor_params *p, const void *Q, const void *k_new,
+                                        const void *v_new, void *arena, float *comp,
+                                        razor_head_desc *desc_dev, void *O, void *stream)
+{
+    using namespace razor;
+    int rc = check_decode_args(p, Q, k_new, v_new, arena, comp, desc_dev, O);
+    if (rc != RAZOR_OK) return rc;
+    int workers = 0;
+    rc = decode_workers(p, &workers);
+    if (rc != RAZOR_OK) return rc;
+    // the layout is cut for the wavefronts this launch really uses, not for the largest count
+    const DecodeWorkspace ws = decode_workspace(*p, workers);
+    if (ws.bytes > (size_t)RAZOR_STATIC_SCRATCH_BYTES)
+        return capacity_failure("razor_decode_attn_static: this step needs more split-K scratch than "
+                                "RAZOR_STATIC_SCRATCH_BYTES; lower n_workers or call razor_decode_attn");
+    void *ptr = nullptr;
+    rc = static_scratch(&ptr);
+    if (rc != RAZOR_OK) return rc;
+    return launch_decode(p, Q, k_new, v_new, arena, comp, desc_dev, O, ptr, ws, workers, stream);
 }
 
 #ifdef RAZOR_TIMELINE

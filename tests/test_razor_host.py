@@ -41,7 +41,7 @@ def test_library_exports_every_declared_symbol():
     for name in sorted(os.listdir(os.path.join(ROOT, "include"))):       # razor.h and razor_bench.h
         header = open(os.path.join(ROOT, "include", name)).read()
         declared |= set(re.findall(r"^RAZOR_API [^;]*?\b(razor_[a-z_]+)\s*\(", header, re.M | re.S))
-    assert len(declared) == 11 and declared == set(razor.EXPORTS)
+    assert len(declared) == 12 and declared == set(razor.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
     assert razor.razor_strerror(razor.RAZOR_OK) == "ok"
@@ -145,6 +145,12 @@ def test_bad_arguments_are_rejected_before_any_gpu_work():
     assert L.razor_decode_attn(pp, fake, None, None, fake, fake, fake + 8, fake, fake, 1 << 30, None) == razor.RAZOR_EINVAL
     assert L.razor_compress(pp, fake, fake, 4 * 100 * 128, 100 * 128, 128, seq.ctypes.data, mask.ctypes.data, fake,
                             fake, fake + 8, None, None, fake, 1 << 30, None) == razor.RAZOR_EINVAL
+    # the variant that owns its scratch: same checks, and a step that does not fit is refused
+    assert L.razor_decode_attn_static(pp, None, None, None, fake, fake, fake, fake, None) == razor.RAZOR_EINVAL
+    assert L.razor_decode_attn_static(pp, fake, fake, None, fake, fake, fake, fake, None) == razor.RAZOR_EINVAL
+    big = params(batch=64, n_kv_heads=8, n_q_heads=128, n_workers=razor.RAZOR_MAX_WORKERS)   # 8704 slots x 16 x 130 floats
+    assert L.razor_decode_attn_static(ctypes.byref(big), fake, None, None, fake, fake, fake, fake, None) == razor.RAZOR_ECAPACITY
+    assert "razor_decode_attn_static" in razor.razor_strerror(razor.RAZOR_ECAPACITY)
 
 
 def test_more_heads_than_a_launch_can_index_are_rejected_up_front():
@@ -164,6 +170,7 @@ def test_more_heads_than_a_launch_can_index_are_rejected_up_front():
     assert L.razor_column_sums(pp, fake, fake, 8 * 40 * 128, 40 * 128, 128, seq.ctypes.data, fake, fake, 1 << 40,
                                None) == razor.RAZOR_EINVAL
     assert L.razor_decode_attn(pp, fake, None, None, fake, fake, fake, fake, fake, 1 << 40, None) == razor.RAZOR_EINVAL
+    assert L.razor_decode_attn_static(pp, fake, None, None, fake, fake, fake, fake, None) == razor.RAZOR_EINVAL
 
 
 def test_missing_library_fails_loudly(monkeypatch):

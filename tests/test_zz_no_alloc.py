@@ -1,0 +1,52 @@
+"""razor_decode_attn_static -- the decode entry point for callers that cannot allocate -- against
+razor_decode_attn on the same caches: two calls in a row through the C ABI, the second on a
+smaller input, each compared bit for bit (the kernels are the same; only the scratch differs)
+and against the fp64 oracle at the usual bars."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_15891_amd as razor
+from oracle import razor_oracle as orc
+from paper_2407_15891_amd.workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def one_call(cfg, context, window, batch, steps):
+    w = make_workload(cfg, DEV, context=context, window=window, batch=batch, max_new=steps)
+    a = razor.RazorCache.from_workload(w); a.compress(w.K, w.V)      # read through razor_decode_attn
+    b = razor.RazorCache.from_workload(w); b.compress(w.K, w.V)      # read through razor_decode_attn_static
+    oc = orc.OracleCache(w.K.cpu(), w.V.cpu(), w.seq_lens, w.mask, w.n_sink, w.window, max_new=steps)
+    out_b = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=DEV)
+    stream = torch.cuda.current_stream().cuda_stream
+    for t in range(steps):
+        Q, k, v = w.step_inputs(t)
+        out_a = a.decode(Q, k, v)
+        rc = razor.razor_decode_attn_static(b.params, Q, k, v, b.arena, b.comp, b.desc_dev, out_b, stream)
+        assert rc == razor.RAZOR_OK, razor.razor_strerror(rc)
+        torch.cuda.synchronize()
+        assert torch.equal(out_a, out_b), f"cfg {cfg} step {t}: static-scratch result differs"
+        oc.append(k.cpu(), v.cpu())
+        ref = oc.decode(Q.cpu(), w.scale)
+        got = out_b.cpu().numpy().astype(np.float64)
+        assert np.abs(got - ref).max() <= 2e-3
+        assert (np.linalg.norm(got - ref, axis=-1) / np.linalg.norm(ref, axis=-1)).max() <= 1e-2
+    np.testing.assert_array_equal(a.desc(), b.desc())
+    assert torch.equal(a.arena, b.arena) and torch.equal(a.comp, b.comp)
+
+
+def test_static_scratch_entry_point_matches_workspace_entry_point():
+    print("no-alloc decode: config 3 shape, 20000-token context, batch 3, then config 1 shape, 300 tokens", flush=True)
+    one_call(3, 20000, 2500, 3, 3)        # fills ~1000 partial-state slots of the library's scratch
+    one_call(1, 300, 40, 1, 3)            # smaller input right after: stale scratch contents must not matter
+
+
+def test_static_scratch_refuses_steps_that_do_not_fit():
+    w = make_workload(4, DEV, context=600, window=64, batch=16, max_new=1)
+    c = razor.RazorCache.from_workload(w, n_workers=8192); c.compress(w.K, w.V)   # 8320 slots x 8 x 130 floats
+    Q, _, _ = w.step_inputs(0, append=False)
+    out = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=DEV)
+    rc = razor.razor_decode_attn_static(c.params, Q, None, None, c.arena, c.comp, c.desc_dev, out, 0)
+    assert rc == razor.RAZOR_ECAPACITY and "RAZOR_STATIC_SCRATCH_BYTES" in razor.razor_strerror(rc)
