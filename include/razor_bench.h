@@ -27,7 +27,9 @@ RAZOR_API int razor_profile_events(void *ev_start, void *ev_stop);
 /* How a probe kernel hands 4 KB pieces to its W wavefronts (`pattern`): 0 = wavefront w gets one
  * contiguous range; n >= 1 (at most 65536) = the buffer is cut into chunks of n pieces and wavefront
  * w gets chunks w, w + W, w + 2W, ..., so that at any moment the chip works inside one moving window
- * of W * n pieces. */
+ * of W * n pieces; -G (G >= 1, at most RAZOR_MAX_WORKERS) = the wavefronts form groups of G, every group
+ * owns one contiguous range, and wave j of a group takes pieces j, j + G, j + 2G, ... of that range
+ * (W / G moving windows of G pieces; G is lowered to the next divisor of W). */
 #define RAZOR_PROBE_CONTIGUOUS 0
 #define RAZOR_PROBE_INTERLEAVED 1
 

@@ -22,6 +22,7 @@ namespace {
 #define RAZOR_LDS_PAD 0
 #endif
 constexpr int kDescPerLaunch = 64;
+constexpr int kStagedSums = 12;   // partial sums a wave of sum_dropped_kernel parks in LDS before it writes them out
 struct DescBatch {
     razor_head_desc d[kDescPerLaunch];
     int32_t sum_prefix[kDescPerLaunch];   // first partial-sum slot of each head (see compress_kernel)
@@ -291,16 +292,25 @@ __global__ __launch_bounds__(256) void sum_dropped_kernel(
         return r;
     };
 
-    // the wave's blocks in order: chunk ordinal j, block g of the axis, hi = end of the chunk
+    // the wave's blocks in order: chunk ordinal j, block g of the axis, hi = end of the chunk.  The
+    // chunk bounds floor(c T / M) and floor((c + 1) T / M) are carried as quotient and remainder and
+    // advanced by n_workers chunks at a time with additions only (a 64-bit division per chunk costs
+    // a wave about a microsecond).
+    const int64_t step_q = (int64_t)n_workers * T / M, step_r = (int64_t)n_workers * T % M;
+    int64_t lo_q = (int64_t)w * T / M, lo_r = (int64_t)w * T % M;             // chunk w
+    int64_t hi_q = ((int64_t)w + 1) * T / M, hi_r = ((int64_t)w + 1) * T % M;
     int j = -1;
     int64_t g = 0, hi = 0;
     auto next_block = [&]() -> bool {   // moves to the next block; false when the wave is done
         ++g;
         while (g >= hi) {
             if (++j >= chunks_per_worker) return false;
-            const int64_t c = w + (int64_t)j * n_workers;
-            g = c * T / M;
-            hi = (c + 1) * T / M;
+            g = lo_q;
+            hi = hi_q;
+            lo_q += step_q; lo_r += step_r;
+            if (lo_r >= M) { lo_r -= M; ++lo_q; }
+            hi_q += step_q; hi_r += step_r;
+            if (hi_r >= M) { hi_r -= M; ++hi_q; }
         }
         return true;
     };
@@ -334,11 +344,33 @@ __global__ __launch_bounds__(256) void sum_dropped_kernel(
     fetch(meta[0], kb[0], vb[0]);
     fetch(meta[1], kb[1], vb[1]);
 
+    // Partial sums wait in LDS until the wave has issued its last load: a store in the middle of the
+    // stream sits in the same in-order counter as the loads behind it, so the wave would wait for
+    // its write acknowledgement before it could use those loads (measured: 2 us per chunk).
+    __shared__ float staged[4][kStagedSums][2 * D];
+    __shared__ int staged_slot[4][kStagedSums];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int n_staged = 0;
+    auto drain = [&]() {   // LDS -> partial sums, 16 bytes per lane and step
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int i = 0; i < n_staged; ++i) {
+            float *dst = partial + (size_t)staged_slot[wave][i] * 2 * D;
+            for (int c = lane * 4; c < 2 * D; c += 256)
+                *reinterpret_cast<float4 *>(dst + c) = *reinterpret_cast<const float4 *>(&staged[wave][i][c]);
+        }
+        __builtin_amdgcn_wave_barrier();
+        n_staged = 0;
+    };
     Summer sum;
     int open_slot = -1;
     auto flush = [&]() {
         sum.reduce();
-        if (prow == 0) sum.store(partial + (size_t)open_slot * 2 * D, piece);
+        if (n_staged == kStagedSums) drain();
+        if (prow == 0) sum.store(staged[wave][n_staged], piece);
+        if (lane == 0) staged_slot[wave][n_staged] = open_slot;
+        ++n_staged;
         sum.clear();
     };
     while (meta[0].valid) {
@@ -355,6 +387,7 @@ __global__ __launch_bounds__(256) void sum_dropped_kernel(
         }
     }
     if (open_slot >= 0) flush();
+    drain();
 }
 
 // Cache row t of a head sits at source position t (sinks, or nothing dropped) or

@@ -29,13 +29,27 @@ __device__ __forceinline__ void probe_store(u32x4 *p, const u32x4 v)
     else *p = v;
 }
 
-// Piece k of wavefront w: its own contiguous range [w * per, ...), or -- interleaved in chunks of
-// `chunk` pieces -- the pieces of chunks w, w + n_waves, w + 2 n_waves, ...
+// Piece k of wavefront w.  chunk = 0, group = 0: its own contiguous range [w * per, ...).
+// chunk = n: interleaved in chunks of n pieces -- the pieces of chunks w, w + n_waves, w + 2 n_waves, ...
+// group = G: the wavefronts form groups of G; a group owns one contiguous range and its G waves
+// take that range's pieces in turn (wave j of the group: pieces j, j + G, j + 2 G, ... of it).
 struct PieceMap {
     int64_t n_pieces, per, n_waves;
-    int chunk;   // 0: contiguous
+    int chunk, group;
+    __device__ __forceinline__ void group_range(int64_t w, int64_t &lo, int64_t &hi) const
+    {
+        const int64_t n_groups = (n_waves + group - 1) / group, per_group = (n_pieces + n_groups - 1) / n_groups;
+        lo = w / group * per_group;
+        hi = lo + per_group < n_pieces ? lo + per_group : n_pieces;
+    }
     __device__ __forceinline__ int64_t count(int64_t w) const
     {
+        if (group) {
+            int64_t lo, hi;
+            group_range(w, lo, hi);
+            const int64_t j = w % group;
+            return hi - lo > j ? (hi - lo - j + group - 1) / group : 0;
+        }
         if (chunk) {
             const int64_t n_chunks = (n_pieces + chunk - 1) / chunk;
             if (w >= n_chunks) return 0;
@@ -47,9 +61,47 @@ struct PieceMap {
         const int64_t lo = w * per, hi = lo + per < n_pieces ? lo + per : n_pieces;
         return hi > lo ? hi - lo : 0;
     }
-    __device__ __forceinline__ int64_t piece(int64_t w, int64_t k) const
+    // piece k of wavefront w = start + (k / run) * jump + k % run for every hand-out: `run` consecutive
+    // pieces, then a jump (contiguous: one run; grouped: runs of one piece, G apart)
+    __device__ __forceinline__ void walk(int64_t w, int64_t &start, int &run, int64_t &jump) const
     {
-        return chunk ? (w + k / chunk * n_waves) * chunk + k % chunk : w * per + k;
+        if (group) {
+            int64_t lo, hi;
+            group_range(w, lo, hi);
+            start = lo + w % group;
+            run = 1;
+            jump = group;
+        } else if (chunk) {
+            start = w * chunk;
+            run = chunk;
+            jump = n_waves * chunk;
+        } else {
+            start = w * per;
+            run = 0x7fffffff;
+            jump = 0;
+        }
+    }
+};
+
+// The pieces of one wavefront in order, without a division per piece.
+struct PieceWalk {
+    int64_t at, jump;
+    int run, left;
+    __device__ __forceinline__ PieceWalk(const PieceMap &map, int64_t w)
+    {
+        map.walk(w, at, run, jump);
+        left = run;
+    }
+    __device__ __forceinline__ int64_t next()   // the current piece; moves on
+    {
+        const int64_t p = at;
+        if (--left == 0) {
+            at += jump - (run - 1);
+            left = run;
+        } else {
+            ++at;
+        }
+        return p;
     }
 };
 
@@ -61,11 +113,13 @@ __global__ __launch_bounds__(256) void read_stream_kernel(const u32x4 *__restric
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t n = map.count(w);
     uint32_t acc = 0;
+    PieceWalk walk(map, w);
+    int64_t piece = 0;
     for (int64_t k = 0; k < n; k += DEPTH) {
         u32x4 v[DEPTH][4];
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u) {
-            const int64_t piece = map.piece(w, k + u < n ? k + u : n - 1);
+            if (k + u < n) piece = walk.next();   // past the end: the last piece once more
             const u32x4 *q = p + piece * (kPieceBytes / 16) + lane;
 #pragma unroll
             for (int s = 0; s < 4; ++s) v[u][s] = probe_load<NT>(q + s * 64);
@@ -85,13 +139,16 @@ __global__ __launch_bounds__(256) void copy_stream_kernel(u32x4 *__restrict__ ds
     const int lane = threadIdx.x & 63;
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t n = map.count(w);
+    PieceWalk walk(map, w);
     for (int64_t k = 0; k < n; k += 2) {
         u32x4 v[2][4];
+        int64_t piece[2] = {0, 0};
         const int m = k + 1 < n ? 2 : 1;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             if (u < m) {
-                const u32x4 *q = src + map.piece(w, k + u) * (kPieceBytes / 16) + lane;
+                piece[u] = walk.next();
+                const u32x4 *q = src + piece[u] * (kPieceBytes / 16) + lane;
 #pragma unroll
                 for (int s = 0; s < 4; ++s) v[u][s] = probe_load<NT_LOAD>(q + s * 64);
             }
@@ -99,7 +156,7 @@ __global__ __launch_bounds__(256) void copy_stream_kernel(u32x4 *__restrict__ ds
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             if (u < m) {
-                u32x4 *q = dst + map.piece(w, k + u) * (kPieceBytes / 16) + lane;
+                u32x4 *q = dst + piece[u] * (kPieceBytes / 16) + lane;
 #pragma unroll
                 for (int s = 0; s < 4; ++s) probe_store<NT_STORE>(q + s * 64, v[u][s]);
             }
@@ -111,7 +168,7 @@ __global__ __launch_bounds__(256) void copy_stream_kernel(u32x4 *__restrict__ ds
 int probe_setup(size_t bytes, int n_workers, int pattern, int &workers, PieceMap &map)
 {
     if (bytes < (size_t)kPieceBytes || n_workers < 0 || n_workers > RAZOR_MAX_WORKERS) return RAZOR_EINVAL;
-    if (pattern < 0 || pattern > 65536) return RAZOR_EINVAL;
+    if (pattern < -RAZOR_MAX_WORKERS || pattern > 65536) return RAZOR_EINVAL;
     workers = n_workers;
     if (workers == 0) {
         const int rc = auto_workers(&workers);
@@ -121,7 +178,9 @@ int probe_setup(size_t bytes, int n_workers, int pattern, int &workers, PieceMap
     map.n_pieces = (int64_t)(bytes / kPieceBytes);        // a tail shorter than a piece is not touched
     map.per = (map.n_pieces + workers - 1) / workers;
     map.n_waves = workers;
-    map.chunk = pattern;
+    map.chunk = pattern > 0 ? pattern : 0;
+    map.group = pattern < 0 ? std::min(-pattern, workers) : 0;
+    while (map.group > 1 && workers % map.group) --map.group;   // whole groups only
     return RAZOR_OK;
 }
 

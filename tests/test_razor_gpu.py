@@ -650,7 +650,7 @@ def test_read_stream_probe_runs_on_odd_sizes():
     buf = torch.ones(5 * 4096 * 1031 + 777, dtype=torch.uint8, device=DEV)
     sink = torch.zeros(4 * razor.RAZOR_MAX_WORKERS, dtype=torch.uint8, device=DEV)
     for nbytes, workers in ((4096, 0), (4096 * 3 + 5, 4), (buf.numel(), 0), (buf.numel(), 1000), (buf.numel(), 8192)):
-        for pattern in (razor.RAZOR_PROBE_CONTIGUOUS, razor.RAZOR_PROBE_INTERLEAVED, 7, 64):
+        for pattern in (razor.RAZOR_PROBE_CONTIGUOUS, razor.RAZOR_PROBE_INTERLEAVED, 7, 64, -5, -32):
             for depth, nt in ((1, 1), (2, 0), (4, 1), (8, 0)):
                 assert razor.razor_probe_read_stream(buf, nbytes, workers, pattern, depth, nt, sink) == razor.RAZOR_OK
     torch.cuda.synchronize()
@@ -660,7 +660,7 @@ def test_read_stream_probe_runs_on_odd_sizes():
 def test_copy_probe_copies_whole_pieces_and_nothing_else():
     src = torch.randint(0, 255, (4096 * 517 + 100,), dtype=torch.uint8, device=DEV)
     for workers in (0, 4, 1000, 8192):
-        for pattern in (razor.RAZOR_PROBE_CONTIGUOUS, razor.RAZOR_PROBE_INTERLEAVED, 5, 100):
+        for pattern in (razor.RAZOR_PROBE_CONTIGUOUS, razor.RAZOR_PROBE_INTERLEAVED, 5, 100, -3, -64):
             for hints in range(4):
                 dst = torch.zeros_like(src)
                 assert razor.razor_probe_copy(dst, src, src.numel(), workers, pattern, hints) == razor.RAZOR_OK

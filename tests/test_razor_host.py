@@ -303,7 +303,7 @@ def test_read_stream_probe_arguments_are_checked():
     assert L.razor_probe_read_stream(ctypes.c_void_p(0x1004), 1 << 20, 0, 0, 2, 1, fake, None) == razor.RAZOR_EINVAL
     assert L.razor_probe_read_stream(fake, 100, 0, 0, 2, 1, fake, None) == razor.RAZOR_EINVAL     # less than one piece
     assert L.razor_probe_read_stream(fake, 1 << 20, -3, 0, 2, 1, fake, None) == razor.RAZOR_EINVAL
-    assert L.razor_probe_read_stream(fake, 1 << 20, 0, -1, 2, 1, fake, None) == razor.RAZOR_EINVAL  # unknown pattern
+    assert L.razor_probe_read_stream(fake, 1 << 20, 0, -9000, 2, 1, fake, None) == razor.RAZOR_EINVAL  # unknown pattern
     assert L.razor_probe_read_stream(fake, 1 << 20, 0, 0, 3, 1, fake, None) == razor.RAZOR_EINVAL  # unsupported depth
     far = ctypes.c_void_p(0x10000000)
     assert L.razor_probe_copy(None, fake, 1 << 20, 0, 0, 3, None) == razor.RAZOR_EINVAL
