@@ -601,11 +601,18 @@ __device__ __forceinline__ float load_q(const void *Q, int dtype, int64_t idx)
     return __uint_as_float((uint32_t) static_cast<const uint16_t *>(Q)[idx] << 16);
 }
 
-// One workgroup per query head.  Eq.(5): the compensation token is one more softmax
-// entry with logit scale * q.khat + ln N_d and value vhat.  The partial states of the head's
-// segments are merged in one pass: 32 slot groups each fold their slots (in slot order) into
-// a running state, the 32 states are merged around their common maximum in group order.
+// One workgroup per query head.  Eq.(5): the compensation token is one more softmax entry with
+// logit scale * q.khat + ln N_d and value vhat.  The partial states of the head's segments are
+// merged in one pass: the workgroup's threads form GR slot groups x D / 4 columns (GR = 32 with
+// 1024 threads; launches with many query heads use 256 threads, GR = 8, so that all workgroups
+// are resident at once); each group folds its slots (in slot order) into a running state, the GR
+// states are merged around their common maximum in group order.
 constexpr int kCombineThreads = 1024;
+constexpr int kCombineAhead = 4;   // partial states a thread fetches at a time
+#ifndef RAZOR_COMBINE_WIDE_UP_TO
+#define RAZOR_COMBINE_WIDE_UP_TO 256
+#endif
+constexpr int kCombineWideUpTo = RAZOR_COMBINE_WIDE_UP_TO;   // query heads up to which a workgroup gets 1024 threads
 
 template <int D>
 __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
@@ -615,12 +622,13 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
     const float *__restrict__ part_acc, void *__restrict__ O, int out_dtype, int n_heads,
     int n_kv_heads, int g, int has_new, int use_comp, int sliding, int n_sink, float scale_log2e)
 {
-    constexpr int C4 = D / 4;                    // float4 columns
-    constexpr int GR = kCombineThreads / C4;     // slot groups working in parallel
+    constexpr int C4 = D / 4;                      // float4 columns
+    constexpr int NG = kCombineThreads / C4;       // most slot groups a workgroup can have
     __shared__ float s_comp;
-    __shared__ float s_m[GR], s_l[GR];
-    __shared__ float4 s_acc[GR][C4];
+    __shared__ float s_m[NG], s_l[NG];
+    __shared__ float4 s_acc[NG][C4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int GR = blockDim.x / C4;                // slot groups working in parallel
     const int n_q_heads = n_kv_heads * g;
     const int bj = blockIdx.x, b = bj / n_q_heads, j = bj % n_q_heads;
     const int h = j / g, n = j % g, i = b * n_kv_heads + h;
@@ -637,20 +645,33 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
         for (int c = lane; c < D; c += 64)
             dot += load_q(Q, q_dtype, (int64_t)bj * D + c) * comp[(size_t)i * 2 * D + c];
 
-    // every slot group folds its share of the head's partial states into one running state
+    // every slot group folds its share of the head's partial states into one running state: slots
+    // grp, grp + GR, ... in that order; the loads of kCombineAhead slots are issued together so
+    // that a long head costs a few memory round trips, not one per slot
     const int col = tid % C4, grp = tid / C4;
     float mg = kNegInf, lg = 0.f;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = grp; s < n_slots; s += GR) {
-        const size_t slot = (size_t)(w0 + s + i) * g + n;
-        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + slot * 2);
-        const float4 v = *reinterpret_cast<const float4 *>(part_acc + slot * D + 4 * col);
-        const float m_new = fmaxf(mg, ml.x);
-        const float so = fast_exp2(mg - m_new), sn = fast_exp2(ml.x - m_new);   // mg = -inf gives 0
-        a.x = a.x * so + v.x * sn; a.y = a.y * so + v.y * sn;
-        a.z = a.z * so + v.z * sn; a.w = a.w * so + v.w * sn;
-        lg = lg * so + ml.y * sn;
-        mg = m_new;
+    for (int s0 = grp; s0 < n_slots; s0 += kCombineAhead * GR) {
+        float2 ml[kCombineAhead];
+        float4 v[kCombineAhead];
+#pragma unroll
+        for (int u = 0; u < kCombineAhead; ++u) {
+            const int s = s0 + u * GR < n_slots ? s0 + u * GR : s0;   // past the end: a valid slot, not used
+            const size_t slot = (size_t)(w0 + s + i) * g + n;
+            ml[u] = *reinterpret_cast<const float2 *>(part_ml + slot * 2);
+            v[u] = *reinterpret_cast<const float4 *>(part_acc + slot * D + 4 * col);
+        }
+#pragma unroll
+        for (int u = 0; u < kCombineAhead; ++u) {
+            if (s0 + u * GR < n_slots) {
+                const float m_new = fmaxf(mg, ml[u].x);
+                const float so = fast_exp2(mg - m_new), sn = fast_exp2(ml[u].x - m_new);   // mg = -inf gives 0
+                a.x = a.x * so + v[u].x * sn; a.y = a.y * so + v[u].y * sn;
+                a.z = a.z * so + v[u].z * sn; a.w = a.w * so + v[u].w * sn;
+                lg = lg * so + ml[u].y * sn;
+                mg = m_new;
+            }
+        }
     }
     if (wave == 0) {
 #pragma unroll
@@ -667,12 +688,10 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
         // Eq.(5): the compensation token is one more entry, logit scale * q.khat + ln N_d, value vhat
         const float m_comp = has_comp ? s_comp * scale_log2e + log2f((float)n_dropped) : kNegInf;
         float M = m_comp;
-#pragma unroll 8
         for (int k = 0; k < GR; ++k) M = fmaxf(M, s_m[k]);
         float den = 0.f;
         float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
         if (M > kNegInf) {
-#pragma unroll 8
             for (int k = 0; k < GR; ++k) {
                 const float wgt = fast_exp2(s_m[k] - M);   // empty groups: exp2(-inf) = 0
                 const float4 v = s_acc[k][col];
@@ -796,13 +815,14 @@ int launch_decode(const razor_params *p, const void *Q, const void *k_new, const
     }
     if (g_profile_stop) RAZOR_HIP_CHECK(hipEventRecord(g_profile_stop, s));
 
-    const dim3 cgrid(p->batch * p->n_q_heads);
+    // 1024 threads per query head while those fit the chip in one go, else 256
+    const dim3 cgrid(p->batch * p->n_q_heads), cblock(p->batch * p->n_q_heads <= kCombineWideUpTo ? kCombineThreads : 256);
     if (D == 128)
-        hipLaunchKernelGGL((combine_kernel<128>), cgrid, dim3(kCombineThreads), 0, s, Q, p->dtype, comp,
+        hipLaunchKernelGGL((combine_kernel<128>), cgrid, cblock, 0, s, Q, p->dtype, comp,
                            desc_dev, prefix, nd, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
                            p->use_comp, p->sliding, p->n_sink, sl2e);
     else
-        hipLaunchKernelGGL((combine_kernel<64>), cgrid, dim3(kCombineThreads), 0, s, Q, p->dtype, comp,
+        hipLaunchKernelGGL((combine_kernel<64>), cgrid, cblock, 0, s, Q, p->dtype, comp,
                            desc_dev, prefix, nd, ml, acc, O, p->out_dtype, n_heads, p->n_kv_heads, g, has_new,
                            p->use_comp, p->sliding, p->n_sink, sl2e);
     RAZOR_HIP_CHECK(hipGetLastError());
