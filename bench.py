@@ -266,13 +266,6 @@ def measure_layer(cfg, args, ev, *, steps, warmup, top_level):
         del fcaches
         torch.cuda.empty_cache()
 
-    if args.pmc_calib and top_level:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
     # ---------------- CPU oracle on the host cores (reported baseline, not the target)
     cpu = None
     if not args.no_cpu_baseline:
@@ -850,6 +843,13 @@ def main():
     else:
         log(f"configuration {args.config}")
         top = measure_layer(args.config, args, ev, steps=args.steps, warmup=args.warmup, top_level=True)
+
+    if args.pmc_calib:   # the known-size kernel counter readings are scaled by
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     others = None
     if plain and not args.no_other_configs and args.config == 3:
