@@ -269,7 +269,7 @@ def measure_layer(cfg, args, ev, *, steps, warmup, top_level):
     # ---------------- CPU oracle on the host cores (reported baseline, not the target)
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = oracle_baseline(w, inputs[0], desc0, esize, budget_s=10.0 if top_level else 2.0)
+        cpu = oracle_baseline(w, inputs[0], desc0, esize, budget_s=10.0 if top_level else 2.0, new_cache=new_cache)
 
     byte_ratio = (full["bytes"] / step_bytes) if full else full_rows / kept_rows
     workload = (f"benchmark configuration {cfg}: {w.name}, batch {w.B}, {w.Hq} query / {w.Hkv} KV heads, head_dim "
@@ -398,8 +398,12 @@ def measure_compress(w, caches, new_cache, desc0, esize, ev, stream, full):
     return res
 
 
-def oracle_baseline(w, step_input, desc0, esize, budget_s):
-    """The fp64 oracle's decode of one whole step of the workload, on the host cores."""
+def oracle_baseline(w, step_input, desc0, esize, budget_s, new_cache=None):
+    """The fp64 oracle's decode of one whole step of the workload, on the host cores; with
+    `new_cache` also the error of the library's fp32 output for that step against it."""
+    import numpy as np
+    import torch
+    import paper_2407_15891_amd as razor
     from oracle import razor_oracle as orc
     nb = w.B
     Kc, Vc = w.K[:nb].cpu(), w.V[:nb].cpu()
@@ -416,8 +420,22 @@ def oracle_baseline(w, step_input, desc0, esize, budget_s):
     d_s = desc0[: nb * w.Hkv].copy()
     d_s["rows"] += 1
     sample_bytes = algorithmic_bytes_decode(d_s, w.d, esize, nb, w.Hq, esize)
+    parity = None
+    if new_cache is not None:      # the same step through the library, written out as fp32
+        ref = oc.decode(Qc, w.scale)
+        c = new_cache(w.mask)
+        c.compress(w.K, w.V)
+        c.params.out_dtype = razor.RAZOR_F32
+        got = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=Q.device)
+        c.decode(Q, k, v, out=got)
+        got = got.cpu().numpy().astype(np.float64)
+        parity = {"max_abs": float(np.abs(got - ref).max()),
+                  "row_relative_max": float((np.linalg.norm(got - ref, axis=-1) /
+                                             np.maximum(np.linalg.norm(ref, axis=-1), 1e-30)).max()),
+                  "bar": "max-abs <= 2e-3 and row-relative <= 1e-2 on the fp32 output of this step"}
+        del c
     return {"value": sample_bytes / best / 1e9, "unit": "GB/s", "cores": int(oc.threads), "kind": "oracle",
-            "seconds": best,
+            "seconds": best, "parity_of_this_step": parity,
             "sample": f"one full decode step of the workload ({nb} sequences x {w.Hkv} KV heads, "
                       f"{int(d_s['rows'].sum())} cached rows, {w.Hq} query heads), fp64 C + OpenMP oracle, best of "
                       f"{reps} repetitions; building the oracle's cache (Eq.(4) over the dropped rows) is not timed"}
