@@ -243,10 +243,12 @@ __global__ void segment_sum_kernel(const razor_head_desc *__restrict__ desc, int
 // wavefront w streams chunks w, w + n_workers, w + 2 n_workers, ...: every wave moves the same
 // number of bytes to within one block per chunk, one wave per SIMD keeps the memory system at its
 // best streaming rate, and at any moment the whole chip reads inside one moving window of the
-// source.  The last point matters right after a prefill: rows that were written a moment ago are
-// still dirty in the memory-side cache and come back about a quarter slower; with one contiguous
-// range per wave the waves that own such rows finish last (measured 278 us instead of 197 us for
-// the sums of the 128K benchmark layer), interleaved they cost every wave the same little.
+// source.  The last point matters right after a prefill: the last 256 MB that were written are
+// still dirty in the memory-side cache, reading them forces their write-back, and they come back
+// about a quarter slower (non-temporal traffic in between does not displace them; plain loads of
+// other data do).  With one contiguous range per wave the waves that own such rows finish last
+// (measured 278 us instead of 197 us for the sums of the 128K benchmark layer); interleaved, the
+// inherited write-back costs every wave the same little (about 225 us).
 // Two blocks stay in flight across chunk and head boundaries.  The head table is held in
 // registers (one entry per lane and tile), so finding the head of a block is a few ballots.
 // A chunk's rows of head i go to partial sum c + i (unique, ascending inside a head).
@@ -422,10 +424,10 @@ enum {
 // partial sums of head i are slots sum_prefix[i] .. sum_prefix[i + 1] - 1.  Workgroups are small
 // and handed out in (x, head) order as earlier ones retire: at any moment the chip works inside
 // one moving window of each plane (measured 15 % faster for read + write traffic than a private
-// contiguous range per wave), and rows that cost more to fetch -- rows a prefill kernel has just
-// written are still dirty in the memory-side cache and come back a quarter slower -- delay only
-// the workgroups that meet them instead of becoming the tail of a statically cut launch
-// (measured: 278 us instead of 197 us for the same sums when the cut is static).
+// contiguous range per wave), and rows that cost more to fetch -- the last 256 MB a prefill
+// kernel wrote are still dirty in the memory-side cache; reading them forces their write-back
+// and they come back a quarter slower -- delay only the workgroups that meet them instead of
+// becoming the tail of a statically cut launch.
 template <int RB, int DTYPE, int MODE>   // RB: bytes per row
 __global__ __launch_bounds__(256) void compress_kernel(
     const char *__restrict__ K, const char *__restrict__ V, int64_t stride_b_bytes,
