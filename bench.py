@@ -17,8 +17,8 @@ cores.  `other_configs` carries the same measurements for configurations 1, 2, 4
 permitting, a few steps of configuration 5 (the 32-layer stack).
 
 Other modes: --config N (N = 1..5 as the top-level workload), --head-scores, --wave-timeline
-(per-wave finish times from the debug build), --read-stream-sweep (the memory-system table kept
-under profiles/).
+(per-wave finish times from the debug build), --read-stream-sweep and --read-after-write (the
+memory-system tables kept under profiles/).
 
 Prints one JSON line.
 """
@@ -805,6 +805,40 @@ def run_read_stream_sweep(args, ev):
     print(f"device-to-device copy of the runtime (torch copy_): {2 * nbytes / (ts[len(ts) // 2] * 1e-3) / 1e12:.2f} TB/s")
 
 
+def run_read_after_write(args, ev):
+    """What reading rows costs right after they were written: a 1.4 GiB read stream whose last x MiB were
+    filled by a kernel just before (1 GiB of other traffic first, so that earlier launches leave nothing
+    behind), for the two ways of handing the stream to the wavefronts.  Prints a text table."""
+    import numpy as np
+    import torch
+    import paper_2407_15891_amd as razor
+    dev, MB = "cuda:0", 1 << 20
+    stream = torch.cuda.current_stream().cuda_stream
+    X = torch.ones(3 << 30, dtype=torch.uint8, device=dev)
+    Y = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(4 * razor.RAZOR_MAX_WORKERS, dtype=torch.uint8, device=dev)
+    n = 1400 * MB
+    a, b = ev.create(), ev.create()
+    print(f"read stream of {n // MB} MiB (non-temporal 128-bit loads, one wave per SIMD, two 4 KB pieces in flight), us, median of 5")
+    print(f"{'last MiB just written':>22} {'interleaved 4 KB pieces':>26} {'one contiguous range per wave':>32}")
+    for x in (0, 16, 32, 64, 128, 192, 256, 384, 512, 1024, 1400):
+        row = []
+        for pattern in (razor.RAZOR_PROBE_INTERLEAVED, razor.RAZOR_PROBE_CONTIGUOUS):
+            ts = []
+            for r in range(5):
+                Y.add_(1)
+                Y.add_(1)
+                if x:
+                    X[n - x * MB: n].fill_(2)
+                torch.cuda.synchronize()
+                ev.record(a, stream)
+                assert razor.razor_probe_read_stream(X, n, 0, pattern, 2, 1, sink, stream) == 0
+                ev.record(b, stream)
+                ts.append(ev.elapsed_ms(a, b) * 1e3)
+            row.append(float(np.median(ts)))
+        print(f"{x:>22} {row[0]:>26.1f} {row[1]:>32.1f}", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -834,6 +868,8 @@ def main():
                     "kernel on --config (1..4) from the debug build of the library; prints a text table")
     ap.add_argument("--read-stream-sweep", action="store_true", help="table of what the memory system gives a read "
                     "stream and a copy under the streaming kernels' choices; prints text")
+    ap.add_argument("--read-after-write", action="store_true", help="table of what a read stream pays for rows that "
+                    "a kernel wrote just before (the state a prefill leaves for the compression pass); prints text")
     ap.add_argument("--pmc-calib", action="store_true", help="also run one plain 1 GiB device copy, the "
                     "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
@@ -854,6 +890,8 @@ def main():
         return run_wave_timeline(args)
     if args.read_stream_sweep:
         return run_read_stream_sweep(args, ev)
+    if args.read_after_write:
+        return run_read_after_write(args, ev)
     if args.head_scores:
         return run_head_scores(args, ev)
 
