@@ -50,3 +50,40 @@ def test_static_scratch_refuses_steps_that_do_not_fit():
     out = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=DEV)
     rc = razor.razor_decode_attn_static(c.params, Q, None, None, c.arena, c.comp, c.desc_dev, out, 0)
     assert rc == razor.RAZOR_ECAPACITY and "RAZOR_STATIC_SCRATCH_BYTES" in razor.razor_strerror(rc)
+
+
+def test_static_scratch_entry_point_under_hip_graph_capture():
+    """The callers this entry point is for: a decode step captured into a HIP graph (capture forbids
+    allocation; the call makes none and takes no workspace) and replayed, with eager work between
+    the replays, gives the bits of the eager razor_decode_attn path every time."""
+    print("no-alloc decode captured in a HIP graph and replayed", flush=True)
+    w = make_workload(3, DEV, context=6000, window=700, batch=2, max_new=12)
+    eager = razor.RazorCache.from_workload(w); eager.compress(w.K, w.V)
+    graphed = razor.RazorCache.from_workload(w); graphed.compress(w.K, w.V)
+    side_cache = razor.RazorCache.from_workload(w); side_cache.compress(w.K, w.V)
+    Qs, ks, vs = (torch.empty_like(x) for x in w.step_inputs(0))
+    out_g = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=DEV)
+
+    def static_step(cache):
+        rc = razor.razor_decode_attn_static(cache.params, Qs, ks, vs, cache.arena, cache.comp, cache.desc_dev, out_g,
+                                            torch.cuda.current_stream().cuda_stream)
+        assert rc == razor.RAZOR_OK, razor.razor_strerror(rc)
+    # first call on the device outside the capture (it looks up the scratch array's address), on a side stream
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        static_step(side_cache)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        static_step(graphed)
+    for t in range(8):
+        Q, k, v = w.step_inputs(t)
+        ref = eager.decode(Q, k, v).clone()
+        Qs.copy_(Q); ks.copy_(k); vs.copy_(v)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, ref), f"replay {t}"
+        _ = (w.K[0, 0, :64].float().sum()).item()          # unrelated eager work between replays
+    np.testing.assert_array_equal(graphed.desc()["rows"], eager.desc()["rows"])
