@@ -252,12 +252,14 @@ __global__ void segment_sum_kernel(const razor_head_desc *__restrict__ desc, int
 // Two blocks stay in flight across chunk and head boundaries.  The head table is held in
 // registers (one entry per lane and tile), so finding the head of a block is a few ballots.
 // A chunk's rows of head i go to partial sum c + i (unique, ascending inside a head).
-template <int DTYPE, int D, int TILES>
+template <int DTYPE, int D, int TILES, bool ARGS>   // ARGS: the table comes with the launch (batch), not from memory
 __global__ __launch_bounds__(256) void sum_dropped_kernel(
     const char *__restrict__ K, const char *__restrict__ V, int64_t stride_b_bytes, int64_t stride_h_bytes,
-    int64_t stride_n_bytes, const razor_head_desc *__restrict__ desc, int n_heads, int n_kv_heads, int n_sink,
-    int n_workers, int chunks_per_worker, int32_t *__restrict__ prefix, float *__restrict__ partial)
+    int64_t stride_n_bytes, const DescBatch batch, const razor_head_desc *__restrict__ desc, int n_heads,
+    int n_kv_heads, int n_sink, int n_workers, int chunks_per_worker, int32_t *__restrict__ prefix,
+    float *__restrict__ partial)
 {
+    static_assert(!ARGS || TILES == 1, "a launch carries at most 64 table entries");
     using Summer = RowSummer<DTYPE, D>;
     constexpr int LPR = Summer::LPR, NI = Summer::NI;
     const int lane = threadIdx.x & 63;
@@ -269,7 +271,8 @@ __global__ __launch_bounds__(256) void sum_dropped_kernel(
 #pragma unroll
     for (int t = 0; t < TILES; ++t) {
         const int idx = t * 64 + lane;
-        nd[t] = idx < n_heads ? desc_counts(desc, idx).z : 0;
+        if constexpr (ARGS) nd[t] = idx < n_heads ? batch.d[idx].n_dropped : 0;
+        else nd[t] = idx < n_heads ? desc_counts(desc, idx).z : 0;
         end[t] = carry + wave_inclusive_scan((nd[t] + kBlockRows - 1) / kBlockRows, lane);
         carry = __shfl(end[t], 63);
     }
@@ -407,6 +410,72 @@ enum {
     kSumStreamed = 3   // second level only: the dropped rows were added up by sum_dropped_kernel
 };
 
+// Eq.(4), second level: add the partial sums of a head (interleaved chains, each in index
+// order, then the chains in order, in double) and divide by N_d.  Called by a whole workgroup.
+//   kSumDropped  comp = sum / N_d               (the partial sums cover the dropped rows)
+//   kSumKept     comp = (col_sums - sum) / N_d  (they cover the kept rows: Eq.(4) by complement)
+//   kSumStreamed like kSumDropped, the partial sums being those of sum_dropped_kernel: sum_prefix
+//                then holds the heads' dropped-block prefix and the number of chunks M, and head i
+//                owns the slots c + i of the chunks c that overlap its blocks
+//   kSumNothing  comp = 0
+// comp_lo (sliding mode: low-order parts of the running means) starts at zero.
+template <int D, int MODE>
+__device__ __forceinline__ void finalize_head(const razor_head_desc &e, int head, int n_heads,
+                                              const int32_t *__restrict__ sum_prefix,
+                                              const float *__restrict__ sums, const float *__restrict__ col_sums,
+                                              float *__restrict__ comp, float *__restrict__ comp_lo,
+                                              double *red, int t, int n_threads)
+{
+    // the workgroup's threads: 2 D columns x (n_threads / 2 D) chains; chain c adds the partial sums
+    // first + c, first + c + chains, ... in that order, eight loads at a time
+    constexpr int COLS = 2 * D;
+    const int chains = n_threads / COLS, col = t % COLS, grp = t / COLS;
+    double s = 0.0;
+    if constexpr (MODE != kSumNothing) {
+        int first = sum_prefix[head], last = sum_prefix[head + 1];
+        if constexpr (MODE == kSumStreamed) {
+            // blocks [lo, hi) of the axis; chunk of block g: the largest c with c T / M <= g
+            const int64_t lo = first, hi = last, T = sum_prefix[n_heads], M = sum_prefix[n_heads + 1];
+            first = hi > lo ? (int)(((lo + 1) * M - 1) / T) + head : 0;
+            last = hi > lo ? (int)((hi * M - 1) / T) + head + 1 : 0;
+        }
+        int k = first + grp;
+        for (; k + 7 * chains < last; k += 8 * chains) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = sums[(size_t)(k + chains * u) * COLS + col];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += (double)v[u];
+        }
+        for (; k < last; k += chains) s += (double)sums[(size_t)k * COLS + col];
+    }
+    red[t] = s;
+    __syncthreads();
+    if (grp == 0) {
+        double sum = red[col];
+        for (int c = 1; c < chains; ++c) sum += red[c * COLS + col];
+        float out = 0.f;
+        if ((MODE == kSumDropped || MODE == kSumStreamed) && e.n_dropped > 0) out = (float)(sum / (double)e.n_dropped);
+        if (MODE == kSumKept && e.n_dropped > 0)
+            out = (float)(((double)col_sums[(size_t)head * COLS + col] - sum) / (double)e.n_dropped);
+        comp[(size_t)head * COLS + col] = out;
+        if (comp_lo) comp_lo[(size_t)head * COLS + col] = 0.f;
+    }
+}
+
+// The second level as a launch of its own (the partial sums come from the launch before it).
+constexpr int kFinalThreads = 1024;
+template <int D, int MODE>
+__global__ __launch_bounds__(kFinalThreads) void mean_final_kernel(
+    const razor_head_desc *__restrict__ desc, int n_heads, const int32_t *__restrict__ sum_prefix,
+    const float *__restrict__ sums, const float *__restrict__ col_sums, float *__restrict__ comp,
+    float *__restrict__ comp_lo)
+{
+    __shared__ double red[kFinalThreads];
+    finalize_head<D, MODE>(desc[blockIdx.x], (int)blockIdx.x, n_heads, sum_prefix, sums, col_sums, comp, comp_lo,
+                           red, (int)threadIdx.x, kFinalThreads);
+}
+
 // The whole pass over the source cache in one launch (Algorithm 1 steps 3-4): every valid source
 // row is read once.  Workgroup (x, head) is one of two kinds.
 //
@@ -428,21 +497,50 @@ enum {
 // kernel wrote are still dirty in the memory-side cache; reading them forces their write-back
 // and they come back a quarter slower -- delay only the workgroups that meet them instead of
 // becoming the tail of a statically cut launch.
-template <int RB, int DTYPE, int MODE>   // RB: bytes per row
+//
+// FINAL >= 0 (a final mode of finalize_head; the partial sums it needs are complete before this
+// launch): the second level of Eq.(4) rides along.  The grid has one more row, dispatched first;
+// workgroup (x, 0) finishes head x while the others copy, so neither a launch nor its few
+// microseconds of latency-bound additions are left on the critical path.  ARGS (with FINAL; at most
+// 64 heads): the table comes with the launch instead of from memory, and those workgroups also
+// store it for the decode calls to come -- no launch for the table either.
+template <int RB, int DTYPE, int MODE, int FINAL, bool ARGS>   // RB: bytes per row
 __global__ __launch_bounds__(256) void compress_kernel(
     const char *__restrict__ K, const char *__restrict__ V, int64_t stride_b_bytes,
-    int64_t stride_h_bytes, int64_t stride_n_bytes, const razor_head_desc *__restrict__ desc,
-    int n_kv_heads, int n_sink, char *__restrict__ arena, const int32_t *__restrict__ sum_prefix,
-    float *__restrict__ sums)
+    int64_t stride_h_bytes, int64_t stride_n_bytes, const DescBatch batch, razor_head_desc *__restrict__ desc,
+    int n_heads, int n_kv_heads, int n_sink, char *__restrict__ arena, const int32_t *__restrict__ sum_prefix,
+    float *__restrict__ sums, float *__restrict__ comp, float *__restrict__ comp_lo)
 {
     constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
     constexpr int D = RB / ES;
     using Summer = RowSummer<DTYPE, D>;
     constexpr int LPR = Summer::LPR, RPI = Summer::RPI, NI = Summer::NI, NE = Summer::NE;
+    static_assert(!ARGS || FINAL >= 0, "the table is stored by the workgroups that finish the means");
+    static_assert(2 * D <= 256, "finalize_head needs a thread per column");
     __shared__ uint4 stage[4][kBlockRows * LPR];
     __shared__ float wave_sums[MODE != kSumNothing ? 4 : 1][MODE != kSumNothing ? 2 * D : 1];
-    const int head = blockIdx.y;
-    const razor_head_desc e = desc[head];
+    __shared__ double red[FINAL >= 0 ? 256 : 1];
+    int head = blockIdx.y;
+    if constexpr (FINAL >= 0) {
+        if (head == 0) {   // the row that finishes Eq.(4): one workgroup per head
+            const int hd = blockIdx.x;
+            if (hd >= n_heads) return;
+            razor_head_desc entry;
+            if constexpr (ARGS) {
+                entry = batch.d[hd];
+                if (threadIdx.x == 0) desc[hd] = entry;
+            } else {
+                entry = desc[hd];
+            }
+            finalize_head<D, FINAL>(entry, hd, n_heads, sum_prefix, sums, nullptr, comp, comp_lo, red,
+                                    (int)threadIdx.x, 256);
+            return;
+        }
+        head -= 1;
+    }
+    razor_head_desc e;
+    if constexpr (ARGS) e = batch.d[head];
+    else e = desc[head];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int prow = lane / LPR, piece = lane % LPR;
     const int b = head / n_kv_heads, h = head % n_kv_heads;
@@ -530,58 +628,6 @@ __global__ __launch_bounds__(256) void compress_kernel(
     }
 }
 
-// Eq.(4), second level: add the partial sums of a head (four interleaved chains, each in index
-// order, then the chains in order, in double) and divide by N_d.  blockDim = (2 * D, 4).
-//   kSumDropped  comp = sum / N_d               (the partial sums cover the dropped rows)
-//   kSumKept     comp = (col_sums - sum) / N_d  (they cover the kept rows: Eq.(4) by complement)
-//   kSumStreamed like kSumDropped, the partial sums being those of sum_dropped_kernel: sum_prefix
-//                then holds the heads' dropped-block prefix and the number of chunks M, and head i
-//                owns the slots c + i of the chunks c that overlap its blocks
-//   kSumNothing  comp = 0
-// comp_lo (sliding mode: low-order parts of the running means) starts at zero.
-template <int D, int MODE>
-__global__ void mean_final_kernel(const razor_head_desc *__restrict__ desc, int n_heads,
-                                  const int32_t *__restrict__ sum_prefix,
-                                  const float *__restrict__ sums, const float *__restrict__ col_sums,
-                                  float *__restrict__ comp, float *__restrict__ comp_lo)
-{
-    __shared__ double red[4][2 * D];
-    const int head = blockIdx.x, t = threadIdx.x, grp = threadIdx.y;
-    const razor_head_desc e = desc[head];
-    double s = 0.0;
-    if constexpr (MODE != kSumNothing) {
-        // chain grp takes the partial sums first + grp, first + grp + 4, ...; eight loads are issued
-        // together, the additions keep their order
-        int first = sum_prefix[head], last = sum_prefix[head + 1];
-        if constexpr (MODE == kSumStreamed) {
-            // blocks [lo, hi) of the axis; chunk of block g: the largest c with c T / M <= g
-            const int64_t lo = first, hi = last, T = sum_prefix[n_heads], M = sum_prefix[n_heads + 1];
-            first = hi > lo ? (int)(((lo + 1) * M - 1) / T) + head : 0;
-            last = hi > lo ? (int)((hi * M - 1) / T) + head + 1 : 0;
-        }
-        int k = first + grp;
-        for (; k + 28 < last; k += 32) {
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = sums[(size_t)(k + 4 * u) * 2 * D + t];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) s += (double)v[u];
-        }
-        for (; k < last; k += 4) s += (double)sums[(size_t)k * 2 * D + t];
-    }
-    red[grp][t] = s;
-    __syncthreads();
-    if (grp == 0) {
-        const double sum = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
-        float out = 0.f;
-        if ((MODE == kSumDropped || MODE == kSumStreamed) && e.n_dropped > 0) out = (float)(sum / (double)e.n_dropped);
-        if (MODE == kSumKept && e.n_dropped > 0)
-            out = (float)(((double)col_sums[(size_t)head * 2 * D + t] - sum) / (double)e.n_dropped);
-        comp[(size_t)head * 2 * D + t] = out;
-        if (comp_lo) comp_lo[(size_t)head * 2 * D + t] = 0.f;
-    }
-}
-
 __global__ void kept_index_kernel(const razor_head_desc *__restrict__ desc, int n_sink,
                                   int32_t *__restrict__ kept_idx)
 {
@@ -606,6 +652,21 @@ inline int sum_chunks(const razor_head_desc &e)
     return ((e.n_dropped + kBlockRows - 1) / kBlockRows + kSumBlocks - 1) / kSumBlocks;
 }
 
+// One batch of the table (entries first .. first + 63) with, for `mode`, the partial-sum slots
+// every head owns; `running` carries the slot count across batches.
+DescBatch make_batch(const std::vector<razor_head_desc> &desc, int first, int mode, int32_t &running)
+{
+    DescBatch batch;
+    const int count = std::min(kDescPerLaunch, (int)desc.size() - first);
+    for (int i = 0; i < kDescPerLaunch; ++i) {
+        batch.d[i] = i < count ? desc[(size_t)first + i] : razor_head_desc{};
+        batch.sum_prefix[i] = running;
+        if (i < count && batch.d[i].n_dropped > 0)
+            running += mode == kSumDropped ? sum_chunks(batch.d[i]) : mode == kSumKept ? copy_groups(batch.d[i]) : 0;
+    }
+    return batch;
+}
+
 // Sends the table (and, with `mode`, the partial-sum slots every head owns) to the device.
 void upload_table(const std::vector<razor_head_desc> &desc, int mode, razor_head_desc *desc_dev,
                   int32_t *sum_prefix, hipStream_t stream)
@@ -613,14 +674,8 @@ void upload_table(const std::vector<razor_head_desc> &desc, int mode, razor_head
     const int n_heads = (int)desc.size();
     int32_t running = 0;
     for (int first = 0; first < n_heads; first += kDescPerLaunch) {
-        DescBatch batch;
+        const DescBatch batch = make_batch(desc, first, mode, running);
         const int count = std::min(kDescPerLaunch, n_heads - first);
-        for (int i = 0; i < kDescPerLaunch; ++i) {
-            batch.d[i] = i < count ? desc[(size_t)first + i] : razor_head_desc{};
-            batch.sum_prefix[i] = running;
-            if (i < count && batch.d[i].n_dropped > 0)
-                running += mode == kSumDropped ? sum_chunks(batch.d[i]) : mode == kSumKept ? copy_groups(batch.d[i]) : 0;
-        }
         hipLaunchKernelGGL(upload_desc_kernel, dim3(1), dim3(kDescPerLaunch), 0, stream, batch, first, count,
                            first + count == n_heads ? running : -1, desc_dev,
                            mode == kSumNothing ? nullptr : sum_prefix);
@@ -635,12 +690,16 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
                     int workers, hipStream_t stream)
 {
     constexpr int ES = DTYPE == RAZOR_F32 ? 4 : 2;
+    constexpr int RB = D * ES;
     const int n_heads = (int)desc.size();
     float *comp_lo = p.sliding ? comp + (size_t)n_heads * 2 * D : nullptr;
     const int mode = max_dropped == 0 ? kSumNothing : col_sums ? kSumKept : kSumDropped;
     // Eq.(4) as it stands, up to 256 heads: the dropped rows are streamed by persistent waves, the
-    // copy runs as a launch of its own; beyond that one launch of small workgroups does both
+    // copy is a launch of its own and finishes the means on the side; beyond that one launch of small
+    // workgroups sums and copies.  Up to 64 heads the table travels with those launches.
     const bool streamed = mode == kSumDropped && n_heads <= 256;
+    const bool folded = (streamed || mode == kSumNothing) && n_heads <= 256;
+    const bool by_args = folded && n_heads <= kDescPerLaunch;
     int max_rows = 0, grid_x = 0;
     int64_t dropped_blocks = 0;
     for (const razor_head_desc &e : desc) {
@@ -648,37 +707,52 @@ int launch_compress(const razor_params &p, const char *K, const char *V, int64_t
         grid_x = std::max(grid_x, copy_groups(e) + (mode == kSumDropped && !streamed ? sum_chunks(e) : 0));
         dropped_blocks += (e.n_dropped + kBlockRows - 1) / kBlockRows;
     }
-    upload_table(desc, streamed ? kSumNothing : mode, desc_dev, sum_prefix, stream);
-    const dim3 grid(grid_x, n_heads), final_block(2 * D, 4);
-#define RAZOR_COMPRESS(MODE, FINAL)                                                                            \
-    do {                                                                                                       \
-        if (grid_x > 0)                                                                                        \
-            hipLaunchKernelGGL((compress_kernel<D * ES, DTYPE, MODE>), grid, dim3(256), RAZOR_LDS_PAD, stream, K, V, \
-                               stride_b * ES, stride_h * ES, stride_n * ES, desc_dev, p.n_kv_heads, p.n_sink,  \
-                               arena, sum_prefix, sums);                                                       \
-        hipLaunchKernelGGL((mean_final_kernel<D, FINAL>), dim3(n_heads), final_block, 0, stream, desc_dev,     \
-                           n_heads, sum_prefix, sums, col_sums, comp, comp_lo);                                \
-    } while (0)
+    int32_t running = 0;
+    const DescBatch batch = by_args ? make_batch(desc, 0, kSumNothing, running) : DescBatch{};
+    if (!by_args) upload_table(desc, streamed ? kSumNothing : mode, desc_dev, sum_prefix, stream);
+
+    const int64_t sb = stride_b * ES, sh = stride_h * ES, sn = stride_n * ES;
     if (streamed) {
         // chunks of about kSumBlocks blocks or more, never more chunks than that: their partial sums
         // (chunks + heads slots) then fit what razor_plan reserved
-        workers = (int)std::max<int64_t>(1, std::min<int64_t>(workers, dropped_blocks / kSumBlocks));
-        const int per_worker =
-            (int)std::max<int64_t>(1, std::min<int64_t>(dropped_blocks / ((int64_t)workers * kSumBlocks), 64));
-        const dim3 sgrid((workers + 3) / 4);
-#define RAZOR_SUM(TILES)                                                                                       \
-        hipLaunchKernelGGL((sum_dropped_kernel<DTYPE, D, TILES>), sgrid, dim3(256), 0, stream, K, V,           \
-                           stride_b * ES, stride_h * ES, stride_n * ES, desc_dev, n_heads, p.n_kv_heads,       \
-                           p.n_sink, workers, per_worker, sum_prefix, sums)
-        if (n_heads <= 64) RAZOR_SUM(1);
-        else if (n_heads <= 128) RAZOR_SUM(2);
-        else RAZOR_SUM(4);
+        const int w = (int)std::max<int64_t>(1, std::min<int64_t>(workers, dropped_blocks / kSumBlocks));
+        const int per_worker = (int)std::max<int64_t>(1, std::min<int64_t>(dropped_blocks / ((int64_t)w * kSumBlocks), 64));
+        const dim3 sgrid((w + 3) / 4);
+#define RAZOR_SUM(TILES, ARGS)                                                                                 \
+        hipLaunchKernelGGL((sum_dropped_kernel<DTYPE, D, TILES, ARGS>), sgrid, dim3(256), 0, stream, K, V, sb, sh, \
+                           sn, batch, desc_dev, n_heads, p.n_kv_heads, p.n_sink, w, per_worker, sum_prefix, sums)
+        if (by_args) RAZOR_SUM(1, true);
+        else if (n_heads <= 64) RAZOR_SUM(1, false);
+        else if (n_heads <= 128) RAZOR_SUM(2, false);
+        else RAZOR_SUM(4, false);
 #undef RAZOR_SUM
-        RAZOR_COMPRESS(kSumNothing, kSumStreamed);
-    } else if (mode == kSumDropped) RAZOR_COMPRESS(kSumDropped, kSumDropped);
-    else if (mode == kSumKept) RAZOR_COMPRESS(kSumKept, kSumKept);
-    else RAZOR_COMPRESS(kSumNothing, kSumNothing);
-#undef RAZOR_COMPRESS
+    }
+    // the copy (with the sums it may have to take along), then the second level of Eq.(4) unless it rode along
+#define RAZOR_COPY(MODE, FINAL, ARGS, GX, GY)                                                                  \
+    hipLaunchKernelGGL((compress_kernel<RB, DTYPE, MODE, FINAL, ARGS>), dim3(GX, GY), dim3(256), RAZOR_LDS_PAD, \
+                       stream, K, V, sb, sh, sn, batch, desc_dev, n_heads, p.n_kv_heads, p.n_sink, arena,      \
+                       sum_prefix, sums, comp, comp_lo)
+#define RAZOR_FINAL(FINAL)                                                                                     \
+    hipLaunchKernelGGL((mean_final_kernel<D, FINAL>), dim3(n_heads), dim3(kFinalThreads), 0, stream, desc_dev, \
+                       n_heads, sum_prefix, sums, col_sums, comp, comp_lo)
+    if (folded) {
+        const int gx = std::max(grid_x, n_heads), gy = n_heads + 1;   // row 0 finishes the means
+        if (streamed && by_args) RAZOR_COPY(kSumNothing, kSumStreamed, true, gx, gy);
+        else if (streamed) RAZOR_COPY(kSumNothing, kSumStreamed, false, gx, gy);
+        else if (by_args) RAZOR_COPY(kSumNothing, kSumNothing, true, gx, gy);
+        else RAZOR_COPY(kSumNothing, kSumNothing, false, gx, gy);
+    } else if (mode == kSumDropped) {
+        if (grid_x > 0) RAZOR_COPY(kSumDropped, -1, false, grid_x, n_heads);
+        RAZOR_FINAL(kSumDropped);
+    } else if (mode == kSumKept) {
+        if (grid_x > 0) RAZOR_COPY(kSumKept, -1, false, grid_x, n_heads);
+        RAZOR_FINAL(kSumKept);
+    } else {
+        if (grid_x > 0) RAZOR_COPY(kSumNothing, -1, false, grid_x, n_heads);
+        RAZOR_FINAL(kSumNothing);
+    }
+#undef RAZOR_COPY
+#undef RAZOR_FINAL
     if (kept_idx_dev && max_rows > 0) {
         const int gx = std::min((max_rows + 255) / 256, 64);
         hipLaunchKernelGGL(kept_index_kernel, dim3(gx, n_heads), dim3(256), 0, stream, desc_dev,
