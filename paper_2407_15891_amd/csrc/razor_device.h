@@ -145,7 +145,8 @@ __device__ __forceinline__ void locate_block(F count, const razor_head_desc *__r
 // Wave-cooperative.  Everything a worker needs in one go: the length of the axis, the blocks
 // per worker, this worker's range [lo, hi) and, if that range is not empty, the head that owns
 // block lo with the flattened index of its first block.  With at most 64 heads (the usual
-// case) one load and one scan serve all of it.
+// case) one load and one scan serve all of it; up to 256 heads the loads of the table go out
+// together (a loop of dependent load + scan rounds cost a microsecond per round).
 template <class F>
 __device__ __forceinline__ void plan_range(F count, const razor_head_desc *__restrict__ desc,
                                            int n_heads, int n_workers, int w, int lane, int &total,
@@ -161,6 +162,33 @@ __device__ __forceinline__ void plan_range(F count, const razor_head_desc *__res
         const int c = __popcll(__ballot(end <= lo));
         head = c;
         first = c == 0 ? 0 : __shfl(end, c - 1);
+        return;
+    }
+    if (n_heads <= 256) {   // four loads issued together, four scans, the rest from registers
+        int nb[4], end[4], carry = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) nb[t] = t * 64 + lane < n_heads ? count(desc, t * 64 + lane) : 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            end[t] = carry + wave_inclusive_scan(nb[t], lane);
+            carry = __shfl(end[t], 63);
+        }
+        total = carry;
+        per = blocks_per_worker(total, n_workers);
+        lo = w * per;
+        hi = lo + per < total ? lo + per : total;
+        head = first = 0;
+        if (lo < hi) {   // ends are non-decreasing; lanes past n_heads hold `total` > lo
+            int c = 0;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) c += __popcll(__ballot(end[t] <= lo));
+            head = c;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int v = __shfl(end[t], (c - 1) & 63);
+                if (c > 0 && ((c - 1) >> 6) == t) first = v;
+            }
+        }
         return;
     }
     total = total_blocks(count, desc, n_heads, lane);
