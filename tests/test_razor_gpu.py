@@ -644,6 +644,45 @@ def test_many_heads():
     np.testing.assert_array_equal(cache.desc()["rows"], oc.rows().reshape(-1))
 
 
+@pytest.mark.parametrize("batch,n_kv", [(8, 8), (13, 5), (32, 8), (257, 1)])
+def test_head_count_boundaries(batch, n_kv):
+    """64, 65, 256 and 257 (sequence, head) pairs: the table as a kernel argument / uploaded, the
+    streamed sums with the second level riding in the copy / the sums inside the copy launch."""
+    n_heads = batch * n_kv
+    say(f"{n_heads} (sequence, head) pairs")
+    g, d, N, n_sink, window = 2, 64, 700, 3, 50
+    gen = torch.Generator(device=DEV); gen.manual_seed(1000 + n_heads)
+    K = torch.randn(batch, n_kv, N, d, generator=gen, device=DEV).to(torch.bfloat16)
+    V = torch.randn(batch, n_kv, N, d, generator=gen, device=DEV).to(torch.bfloat16)
+    seq = np.random.default_rng(n_heads).integers(40, N + 1, size=batch).astype(np.int32)
+    seq[0] = N
+    mask = (np.arange(n_kv) % 4 == 1).astype(np.uint8)
+    cache = razor.RazorCache(batch=batch, n_q_heads=n_kv * g, n_kv_heads=n_kv, head_dim=d, seq_lens=seq,
+                             retrieval_mask=mask, n_sink=n_sink, window=window, max_new=2, dtype=torch.bfloat16,
+                             device=DEV, want_kept_idx=True)
+    cache.compress(K, V)
+    oc = orc.OracleCache(K.cpu(), V.cpu(), seq, mask, n_sink, window, max_new=2)
+    desc = cache.desc()
+    np.testing.assert_array_equal(desc, cache.desc_host)
+    comp = cache.comp_tokens().cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(comp[:, :, 0], oc.khat, rtol=0, atol=2e-5)
+    np.testing.assert_allclose(comp[:, :, 1], oc.vhat, rtol=0, atol=2e-5)
+    Kb, Vb = raw_bytes(K), raw_bytes(V)
+    for i in (0, 1, n_heads // 2, n_heads - 2, n_heads - 1):
+        b, h = divmod(i, n_kv)
+        kept = oc.kept_of(b, h)
+        k, v = arena_rows(cache, desc, i)
+        np.testing.assert_array_equal(k, Kb[b, h][kept])
+        np.testing.assert_array_equal(v, Vb[b, h][kept])
+    for t in range(2):
+        Q = torch.randn(batch, n_kv * g, d, generator=gen, device=DEV).to(torch.bfloat16)
+        k = torch.randn(batch, n_kv, d, generator=gen, device=DEV).to(torch.bfloat16)
+        v = torch.randn(batch, n_kv, d, generator=gen, device=DEV).to(torch.bfloat16)
+        out = cache.decode(Q, k, v)
+        oc.append(k.cpu(), v.cpu())
+        check_output(out, oc.decode(Q.cpu(), d ** -0.5), f"{n_heads} pairs step {t}")
+
+
 # ----------------------------------------------------------------- seeded random sweep
 def test_read_stream_probe_runs_on_odd_sizes():
     """The measurement hook reads whole 4 KB pieces inside the buffer whatever the size and worker count."""
