@@ -645,10 +645,14 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
         for (int c = lane; c < D; c += 64)
             dot += load_q(Q, q_dtype, (int64_t)bj * D + c) * comp[(size_t)i * 2 * D + c];
 
+    // vhat is needed last; its load goes out with the others instead of after the barrier
+    const int col = tid % C4, grp = tid / C4;
+    float4 vhat = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (has_comp && grp == 0) vhat = *reinterpret_cast<const float4 *>(comp + ((size_t)i * 2 + 1) * D + 4 * col);
+
     // every slot group folds its share of the head's partial states into one running state: slots
     // grp, grp + GR, ... in that order; the loads of kCombineAhead slots are issued together so
     // that a long head costs a few memory round trips, not one per slot
-    const int col = tid % C4, grp = tid / C4;
     float mg = kNegInf, lg = 0.f;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s0 = grp; s0 < n_slots; s0 += kCombineAhead * GR) {
@@ -700,8 +704,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(
             }
             if (has_comp) {
                 const float wgt = fast_exp2(m_comp - M);
-                const float4 v = *reinterpret_cast<const float4 *>(comp + ((size_t)i * 2 + 1) * D + 4 * col);
-                num.x += wgt * v.x; num.y += wgt * v.y; num.z += wgt * v.z; num.w += wgt * v.w;
+                num.x += wgt * vhat.x; num.y += wgt * vhat.y; num.z += wgt * vhat.z; num.w += wgt * vhat.w;
                 den += wgt;
             }
         }
