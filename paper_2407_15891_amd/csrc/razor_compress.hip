@@ -7,6 +7,15 @@
 // Given the column sums over the whole sequence (razor_column_sums, or a prefill epilogue) the
 // dropped rows are not read: the copy adds up the kept rows it moves and the mean is taken
 // from the difference.
+//
+// Launches of one call, by the number of (sequence, KV head) pairs:
+//   up to 64    sum_dropped_kernel, compress_kernel -- the table travels as a kernel argument of
+//               both, and the second level of Eq.(4) rides in the first grid row of the copy
+//   up to 256   upload_desc_kernel (one per 64 pairs) first; the rest as above
+//   beyond      upload, compress_kernel (copy and first-level sums in one launch), mean_final_kernel
+//   column sums given   upload, compress_kernel (copy + sums of the kept rows), mean_final_kernel
+//   nothing dropped anywhere   (upload,) compress_kernel
+// plus kept_index_kernel when the caller asks for the positions.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
