@@ -42,13 +42,17 @@ __device__ __forceinline__ int wave_sum(int v)
     return v;
 }
 
-__device__ __forceinline__ int wave_inclusive_scan(int v, int lane)
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves (shifts inside rows
+// of 16 lanes, then the last lane of a row broadcast to the rows after it): six vector
+// instructions, where a scan built on __shfl_up is six dependent trips through the LDS crossbar.
+__device__ __forceinline__ int wave_inclusive_scan(int v, int /*lane*/)
 {
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int up = __shfl_up(v, o);
-        if (lane >= o) v += up;
-    }
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
     return v;
 }
 
@@ -170,8 +174,11 @@ __device__ __forceinline__ void plan_range(F count, const razor_head_desc *__res
         for (int t = 0; t < 4; ++t) nb[t] = t * 64 + lane < n_heads ? count(desc, t * 64 + lane) : 0;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            end[t] = carry + wave_inclusive_scan(nb[t], lane);
-            carry = __shfl(end[t], 63);
+            end[t] = carry;
+            if (t * 64 < n_heads) {   // uniform: tiles past the table cost nothing
+                end[t] = carry + wave_inclusive_scan(nb[t], lane);
+                carry = __builtin_amdgcn_readlane(end[t], 63);
+            }
         }
         total = carry;
         per = blocks_per_worker(total, n_workers);
