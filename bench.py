@@ -473,7 +473,7 @@ def measure_stack(args, ev, *, steps, warmup, full_steps, cpu_baseline):
     if free < need:
         return {"skipped": f"needs about {need / 1e9:.0f} GB of device memory for {L} resident layers, "
                            f"{free / 1e9:.0f} GB free"}
-    max_new = 2 * (steps + warmup) + 2
+    max_new = 2 * (steps + warmup) + 12                   # timed, event and kernel passes
     caches, fulls, masks = [], [], []
     compress_ms, comp_bytes = [], 0
     a, b = ev.create(), ev.create()
@@ -537,7 +537,7 @@ def measure_stack(args, ev, *, steps, warmup, full_steps, cpu_baseline):
     run(caches, warmup)
     wall = run(caches, steps)
     step_us = stats_us(run(caches, max(2, steps // 2), "events"))
-    kernel_us = stats_us(run(caches, 2, "kernel"))                # one entry per (step, layer)
+    kernel_us = stats_us(run(caches, max(2, min(steps, 8)), "kernel"))   # one entry per (step, layer)
     appended = warmup + steps // 2
     layer_bytes = [algorithmic_bytes_decode(c.desc_host, w.d, 2, w.B, w.Hq, 2) + appended * w.B * w.Hkv * 2 * w.d * 2
                    for c in caches]
