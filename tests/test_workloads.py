@@ -61,3 +61,33 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_algorithmic_bytes_of_configuration_3_by_hand():
+    """The numerators of the roofline figures, against arithmetic done by hand for configuration 3
+    (Table 2 settings at 131072 tokens: 4 sinks, window 19660; 4 sequences x 8 KV heads, 2 of them
+    retrieval): a compressed head keeps 4 + 19660 rows, a retrieval head all 131072."""
+    import os
+    import sys
+
+    import paper_2407_15891_amd as razor
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import bench
+
+    w = make_workload(3, "cpu", materialize=False)
+    desc = np.zeros(w.B * w.Hkv, razor.DESC_DTYPE)
+    sizes = razor.RazorSizes()
+    p = razor.RazorParams(w.B, w.Hq, w.Hkv, w.d, w.n_sink, w.window, 0, 1, razor.RAZOR_BF16, razor.RAZOR_F32,
+                          w.scale, 0, 0, 0, None, None)
+    assert razor.razor_plan(p, w.seq_lens, w.mask, desc, None, sizes) == 0
+    kept_rows = 4 * (2 * 131072 + 6 * (4 + 19660))
+    assert int(desc["rows"].sum()) == kept_rows == 1_520_512
+    row_bytes = 2 * 128 * 2                                      # K and V, 128 bf16 each
+    by_hand = (kept_rows * row_bytes                              # every cached row once
+               + 4 * 6 * 2 * 128 * 4                              # khat, vhat (fp32) of the 24 compressed heads
+               + 4 * 32 * 128 * 2 + 4 * 32 * 128 * 2              # Q in, O out (bf16)
+               + 32 * 48)                                         # the table
+    assert bench.algorithmic_bytes_decode(desc, w.d, 2, w.B, w.Hq, 2) == by_hand == 778_593_792
+    src_rows = 4 * 8 * 131072
+    assert bench.algorithmic_bytes_compress(desc, w.seq_lens, w.Hkv, w.d, 2) == \
+        (src_rows + kept_rows) * row_bytes + 32 * 2 * 128 * 4
